@@ -1,0 +1,136 @@
+/*
+ * libechoattn -- additive (MLP) attention for MI355X (gfx950), forward and
+ * backward, with the B x Tq x Tk x H tanh feature map recomputed in the
+ * backward pass instead of stashed.
+ *
+ * The layer (Echo paper, Section 2, attention steps 1 and 2; Section 4.1, the
+ * broadcast add + tanh scoring function; Section 5.1, what replaces the T^2 x N
+ * feature map):
+ *
+ *   L_b        = clamp(key_len[b], 0, Tk)
+ *   S[b,i,j]   = sum_h v[h] * tanh(Qp[b,i,h] + Kp[b,j,h])            j <  L_b
+ *   P[b,i,j]   = softmax over j < L_b of S[b,i,:];   exactly 0.0 for j >= L_b
+ *   C[b,i,d]   = sum_j P[b,i,j] * V[b,j,d]
+ *
+ * Backward from dC (Section 3.2: tanh' = 1 - tanh^2; Eq. 2: gradients of the
+ * dense contractions need only their inputs; Section 3.4: the cheap nodes are
+ * re-run when the backward pass starts):
+ *
+ *   dV[b,j,d]  = sum_i P[b,i,j] * dC[b,i,d]
+ *   dP[b,i,j]  = sum_d dC[b,i,d] * V[b,j,d]
+ *   dS[b,i,j]  = P[b,i,j] * (dP[b,i,j] - sum_j' P[b,i,j'] dP[b,i,j'])
+ *   t          = tanh(Qp[b,i,h] + Kp[b,j,h])                (recomputed)
+ *   dQp[b,i,h] = sum_j dS[b,i,j] v[h] (1 - t^2)
+ *   dKp[b,j,h] = sum_i dS[b,i,j] v[h] (1 - t^2)
+ *   dv[h]      = sum_{b,i,j} dS[b,i,j] t
+ *
+ * Conventions common to every call
+ *   - All tensors are row-major, contiguous, innermost index last.
+ *   - Every pointer except the descriptor is DEVICE memory owned by the caller
+ *     and must be 16-byte aligned.  The library never allocates, frees or
+ *     keeps a pointer.
+ *   - Qp, Kp, V, v have the element type desc->in_dtype (fp32, or bf16 stored
+ *     as 16-bit patterns); all arithmetic and every output is fp32.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream) and the call returns without synchronising.  The return
+ *     value reports argument validation and launch errors only.
+ *   - Outputs are overwritten, never accumulated into.  Rows of P, dKp and dV
+ *     at masked keys (j >= L_b) are written as exact zeros.  A sample with
+ *     L_b == 0 yields zeros in all of its outputs and adds nothing to dv.
+ *   - key_len values are clamped, not validated (that would need a sync).
+ *   - Results are bit-identical from run to run: no floating-point atomics.
+ *   - Calls are re-entrant; calls that share a workspace must be ordered by
+ *     the caller (same stream, or events).
+ */
+#ifndef ECHOATTN_H
+#define ECHOATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ECHO_OK = 0,
+    ECHO_ERR_NULL = 1,       /* a required pointer is NULL */
+    ECHO_ERR_SHAPE = 2,      /* a dimension is < 1 or a tensor exceeds 2^31-1 elements per sample / 2^62 in total */
+    ECHO_ERR_DTYPE = 3,      /* in_dtype is not one of echo_dtype_t */
+    ECHO_ERR_WORKSPACE = 4,  /* workspace_bytes smaller than the matching *_workspace_bytes() */
+    ECHO_ERR_ALIGN = 5,      /* a device pointer is not 16-byte aligned */
+    ECHO_ERR_HIP = 6         /* a kernel launch failed (hipGetLastError) */
+} echo_status_t;
+
+typedef enum { ECHO_F32 = 0, ECHO_BF16 = 1 } echo_dtype_t; /* storage of Qp, Kp, V, v */
+
+typedef struct {
+    int32_t B;        /* batch                      */
+    int32_t Tq;       /* queries per sample         */
+    int32_t Tk;       /* keys per sample            */
+    int32_t H;        /* attention hidden size      */
+    int32_t Dv;       /* value width                */
+    int32_t in_dtype; /* echo_dtype_t               */
+} echo_attn_desc_t;
+
+/* Scratch the two passes need, in bytes (host arithmetic; 0 on an invalid
+ * descriptor).  Workspace contents need not survive between calls: the only
+ * state that persists from forward to backward is P (Section 5.1). */
+size_t echo_attn_fwd_workspace_bytes(const echo_attn_desc_t *desc);
+size_t echo_attn_bwd_workspace_bytes(const echo_attn_desc_t *desc);
+
+/* Forward (Section 2, steps 1-2; scoring function of Section 4.1).
+ *   in : Qp [B,Tq,H], Kp [B,Tk,H], V [B,Tk,Dv], v [H]   (in_dtype), key_len [B] int32
+ *   out: context [B,Tq,Dv] fp32, P [B,Tq,Tk] fp32 (keep it for the backward call)
+ * The tanh map is never written to memory. */
+echo_status_t echo_attn_fwd(const echo_attn_desc_t *desc,
+                            const void *Qp, const void *Kp, const void *V, const void *v,
+                            const int32_t *key_len,
+                            float *context, float *P,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/* Backward (Section 3.4 recomputation fused into one kernel as in the
+ * hand-tuned variant of Section 6.1; Section 3.2 and Eq. 2 for the rules).
+ *   in : dContext [B,Tq,Dv] fp32, P [B,Tq,Tk] fp32 as written by echo_attn_fwd,
+ *        and the forward inputs
+ *   out: dQp [B,Tq,H], dKp [B,Tk,H], dV [B,Tk,Dv], dv [H], all fp32 */
+echo_status_t echo_attn_bwd(const echo_attn_desc_t *desc,
+                            const float *dContext, const float *P,
+                            const void *Qp, const void *Kp, const void *V, const void *v,
+                            const int32_t *key_len,
+                            float *dQp, float *dKp, float *dV, float *dv,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/* Comparison only: the baseline behaviour of Section 4.1, which stashes the
+ * output of tanh as a feature map.  Same results as the pair above;
+ * `tanh_map` is B*Tq*Tk*H fp32 (echo_attn_stash_bytes), written by the
+ * forward call and read by the backward call in place of the recomputation. */
+size_t echo_attn_stash_bytes(const echo_attn_desc_t *desc);
+echo_status_t echo_attn_fwd_stash(const echo_attn_desc_t *desc,
+                                  const void *Qp, const void *Kp, const void *V, const void *v,
+                                  const int32_t *key_len,
+                                  float *context, float *P, float *tanh_map,
+                                  void *workspace, size_t workspace_bytes, void *stream);
+echo_status_t echo_attn_bwd_stash(const echo_attn_desc_t *desc,
+                                  const float *dContext, const float *P, const float *tanh_map,
+                                  const void *V, const void *v,
+                                  const int32_t *key_len,
+                                  float *dQp, float *dKp, float *dV, float *dv,
+                                  void *workspace, size_t workspace_bytes, void *stream);
+
+/* Per-kernel timing for the benchmark.  While enabled, every kernel the
+ * library launches from the calling thread is bracketed by HIP events on its
+ * stream.  echo_attn_profile_read() synchronises those events and copies up
+ * to `cap` entries (kernel name, launches, total milliseconds) to HOST arrays,
+ * returns the number of distinct kernels, and clears the record.  Enabling
+ * costs two event records per launch; leave it off otherwise. */
+void echo_attn_profile_enable(int on);
+int  echo_attn_profile_read(const char **names, int *launches, float *total_ms, int cap);
+
+const char *echo_status_string(echo_status_t s);
+const char *echo_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ECHOATTN_H */

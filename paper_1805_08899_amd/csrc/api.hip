@@ -1,0 +1,237 @@
+// C ABI of libechoattn: argument validation, workspace carving and the
+// sequence of kernel launches.  No allocation, no synchronisation.
+#include "../../include/echoattn.h"
+
+#include <hip/hip_runtime.h>
+
+#include <string>
+#include <vector>
+
+#include "kernels.hpp"
+
+namespace {
+
+using echo::AttnShape;
+
+constexpr int kMaxTk = 2048;   // dP rows of 16 queries live in LDS in the softmax-backward kernel
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+echo_status_t check_desc(const echo_attn_desc_t *d, AttnShape *s) {
+    if (!d) return ECHO_ERR_NULL;
+    if (d->in_dtype != ECHO_F32 && d->in_dtype != ECHO_BF16) return ECHO_ERR_DTYPE;
+    if (d->B < 1 || d->Tq < 1 || d->Tk < 1 || d->H < 1 || d->Dv < 1) return ECHO_ERR_SHAPE;
+    if (d->Dv % 4 != 0) return ECHO_ERR_SHAPE;            // value rows are read 16 bytes at a time
+    if (d->Tk > kMaxTk) return ECHO_ERR_SHAPE;
+    if (d->B > 65535) return ECHO_ERR_SHAPE;              // batch is a grid y/z dimension
+    const int64_t lim = (int64_t)1 << 31;
+    const int64_t per_sample[] = {(int64_t)d->Tq * d->H, (int64_t)d->Tk * d->H, (int64_t)d->Tk * d->Dv,
+                                  (int64_t)d->Tq * d->Dv, (int64_t)d->Tq * (d->Tk + 16)};
+    for (int64_t e : per_sample)
+        if (e >= lim) return ECHO_ERR_SHAPE;
+    // the 4-D map index B*Tq*Tk*H must fit 62 bits (it always does once the lines above hold; kept explicit)
+    const long double n4 = (long double)d->B * d->Tq * d->Tk * d->H;
+    if (n4 >= 4.6e18L) return ECHO_ERR_SHAPE;
+    if (s) *s = AttnShape{d->B, d->Tq, d->Tk, d->H, d->Dv, d->in_dtype == ECHO_BF16};
+    return ECHO_OK;
+}
+
+inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+struct BwdWs {
+    size_t ds_off, rowsum_off, dvpart_off, total;
+};
+BwdWs bwd_layout(const AttnShape &s) {
+    BwdWs w;
+    w.ds_off = 0;
+    w.rowsum_off = align_up((size_t)s.B * s.Tq * echo::ds_pitch(s.Tk) * sizeof(float));
+    w.dvpart_off = w.rowsum_off + align_up((size_t)s.B * s.Tq * sizeof(float));
+    w.total = w.dvpart_off + align_up((size_t)s.B * s.H * sizeof(float));
+    return w;
+}
+size_t fwd_bytes(const AttnShape &s) { return align_up((size_t)s.B * s.Tq * s.Tk * sizeof(float)); }
+
+// ---- optional per-kernel timing ------------------------------------------------
+struct ProfRec {
+    const char *name;
+    hipEvent_t t0, t1;
+};
+thread_local bool g_prof_on = false;
+thread_local std::vector<ProfRec> g_prof;
+
+struct Timed {
+    const char *name;
+    hipStream_t st;
+    hipEvent_t t0 = nullptr, t1 = nullptr;
+    Timed(const char *n, hipStream_t s) : name(n), st(s) {
+        if (g_prof_on && hipEventCreate(&t0) == hipSuccess && hipEventCreate(&t1) == hipSuccess)
+            (void)hipEventRecord(t0, st);
+    }
+    ~Timed() {
+        if (t0 && t1) {
+            (void)hipEventRecord(t1, st);
+            g_prof.push_back({name, t0, t1});
+        }
+    }
+};
+
+#define ECHO_LAUNCH(NAME, CALL)                    \
+    do {                                           \
+        hipError_t e_;                             \
+        {                                          \
+            Timed t_(NAME, st);                    \
+            e_ = (CALL);                           \
+        }                                          \
+        if (e_ != hipSuccess) return ECHO_ERR_HIP; \
+    } while (0)
+
+echo_status_t fwd_impl(const echo_attn_desc_t *desc, const void *Qp, const void *Kp, const void *V, const void *v,
+                       const int32_t *key_len, float *context, float *P, float *tmap, bool want_map,
+                       void *workspace, size_t workspace_bytes, void *stream) {
+    AttnShape s;
+    echo_status_t rc = check_desc(desc, &s);
+    if (rc != ECHO_OK) return rc;
+    if (!Qp || !Kp || !V || !v || !key_len || !context || !P || !workspace) return ECHO_ERR_NULL;
+    if (want_map && !tmap) return ECHO_ERR_NULL;
+    const void *ptrs[] = {Qp, Kp, V, v, key_len, context, P, workspace, tmap};
+    for (const void *p : ptrs)
+        if (p && misaligned(p)) return ECHO_ERR_ALIGN;
+    if (workspace_bytes < fwd_bytes(s)) return ECHO_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float *S = static_cast<float *>(workspace);
+    ECHO_LAUNCH(want_map ? "score_stash" : "score",
+                echo::launch_score(s, Qp, Kp, v, key_len, S, want_map ? tmap : nullptr, st));
+    ECHO_LAUNCH("softmax", echo::launch_softmax(s, S, key_len, P, st));
+    ECHO_LAUNCH("context", echo::launch_context(s, P, V, key_len, context, st));
+    return ECHO_OK;
+}
+
+echo_status_t bwd_impl(const echo_attn_desc_t *desc, const float *dContext, const float *P, const float *tmap,
+                       bool use_map, const void *Qp, const void *Kp, const void *V, const void *v,
+                       const int32_t *key_len, float *dQp, float *dKp, float *dV, float *dv, void *workspace,
+                       size_t workspace_bytes, void *stream) {
+    AttnShape s;
+    echo_status_t rc = check_desc(desc, &s);
+    if (rc != ECHO_OK) return rc;
+    if (!dContext || !P || !V || !v || !key_len || !dQp || !dKp || !dV || !dv || !workspace) return ECHO_ERR_NULL;
+    if (use_map ? !tmap : (!Qp || !Kp)) return ECHO_ERR_NULL;
+    const void *ptrs[] = {dContext, P, tmap, Qp, Kp, V, v, key_len, dQp, dKp, dV, dv, workspace};
+    for (const void *p : ptrs)
+        if (p && misaligned(p)) return ECHO_ERR_ALIGN;
+    const BwdWs lay = bwd_layout(s);
+    if (workspace_bytes < lay.total) return ECHO_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    float *dS = reinterpret_cast<float *>(ws + lay.ds_off);
+    float *rowsum = reinterpret_cast<float *>(ws + lay.rowsum_off);
+    float *dv_part = reinterpret_cast<float *>(ws + lay.dvpart_off);
+    ECHO_LAUNCH("dvalue", echo::launch_dvalue(s, P, dContext, key_len, dV, st));
+    ECHO_LAUNCH("dscore", echo::launch_dscore(s, dContext, V, P, key_len, dS, rowsum, st));
+    ECHO_LAUNCH(use_map ? "recompute_stash" : "recompute",
+                echo::launch_recompute(s, Qp, Kp, v, key_len, dS, use_map ? tmap : nullptr, dQp, dKp, dv_part, st));
+    ECHO_LAUNCH("dv_reduce", echo::launch_dv_reduce(s, dv_part, rowsum, dv, st));
+    return ECHO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t echo_attn_fwd_workspace_bytes(const echo_attn_desc_t *desc) {
+    AttnShape s;
+    return check_desc(desc, &s) == ECHO_OK ? fwd_bytes(s) : 0;
+}
+
+size_t echo_attn_bwd_workspace_bytes(const echo_attn_desc_t *desc) {
+    AttnShape s;
+    return check_desc(desc, &s) == ECHO_OK ? bwd_layout(s).total : 0;
+}
+
+size_t echo_attn_stash_bytes(const echo_attn_desc_t *desc) {
+    AttnShape s;
+    if (check_desc(desc, &s) != ECHO_OK) return 0;
+    return (size_t)s.B * s.Tq * s.Tk * s.H * sizeof(float);
+}
+
+echo_status_t echo_attn_fwd(const echo_attn_desc_t *desc, const void *Qp, const void *Kp, const void *V,
+                            const void *v, const int32_t *key_len, float *context, float *P, void *workspace,
+                            size_t workspace_bytes, void *stream) {
+    return fwd_impl(desc, Qp, Kp, V, v, key_len, context, P, nullptr, false, workspace, workspace_bytes, stream);
+}
+
+echo_status_t echo_attn_bwd(const echo_attn_desc_t *desc, const float *dContext, const float *P, const void *Qp,
+                            const void *Kp, const void *V, const void *v, const int32_t *key_len, float *dQp,
+                            float *dKp, float *dV, float *dv, void *workspace, size_t workspace_bytes,
+                            void *stream) {
+    return bwd_impl(desc, dContext, P, nullptr, false, Qp, Kp, V, v, key_len, dQp, dKp, dV, dv, workspace,
+                    workspace_bytes, stream);
+}
+
+echo_status_t echo_attn_fwd_stash(const echo_attn_desc_t *desc, const void *Qp, const void *Kp, const void *V,
+                                  const void *v, const int32_t *key_len, float *context, float *P,
+                                  float *tanh_map, void *workspace, size_t workspace_bytes, void *stream) {
+    return fwd_impl(desc, Qp, Kp, V, v, key_len, context, P, tanh_map, true, workspace, workspace_bytes, stream);
+}
+
+echo_status_t echo_attn_bwd_stash(const echo_attn_desc_t *desc, const float *dContext, const float *P,
+                                  const float *tanh_map, const void *V, const void *v, const int32_t *key_len,
+                                  float *dQp, float *dKp, float *dV, float *dv, void *workspace,
+                                  size_t workspace_bytes, void *stream) {
+    return bwd_impl(desc, dContext, P, tanh_map, true, nullptr, nullptr, V, v, key_len, dQp, dKp, dV, dv,
+                    workspace, workspace_bytes, stream);
+}
+
+void echo_attn_profile_enable(int on) {
+    g_prof_on = on != 0;
+    if (!on) {
+        for (auto &r : g_prof) {
+            (void)hipEventDestroy(r.t0);
+            (void)hipEventDestroy(r.t1);
+        }
+        g_prof.clear();
+    }
+}
+
+int echo_attn_profile_read(const char **names, int *launches, float *total_ms, int cap) {
+    int n = 0;
+    for (auto &r : g_prof) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.t1) == hipSuccess) (void)hipEventElapsedTime(&ms, r.t0, r.t1);
+        (void)hipEventDestroy(r.t0);
+        (void)hipEventDestroy(r.t1);
+        int k = 0;
+        for (; k < n && k < cap; ++k)
+            if (names[k] == r.name) break;
+        if (k == n) {
+            if (n < cap) {
+                names[n] = r.name;
+                launches[n] = 0;
+                total_ms[n] = 0.f;
+            }
+            ++n;
+        }
+        if (k < cap) {
+            launches[k] += 1;
+            total_ms[k] += ms;
+        }
+    }
+    g_prof.clear();
+    return n;
+}
+
+const char *echo_status_string(echo_status_t s) {
+    switch (s) {
+        case ECHO_OK: return "ok";
+        case ECHO_ERR_NULL: return "null pointer";
+        case ECHO_ERR_SHAPE: return "bad shape";
+        case ECHO_ERR_DTYPE: return "bad dtype";
+        case ECHO_ERR_WORKSPACE: return "workspace too small";
+        case ECHO_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case ECHO_ERR_HIP: return "HIP launch error";
+    }
+    return "unknown status";
+}
+
+const char *echo_version(void) { return "libechoattn 0.1 (gfx950)"; }
+
+}  // extern "C"

@@ -1,0 +1,181 @@
+// The dense contractions of the layer on the matrix cores, fp32 in and out
+// (v_mfma_f32_16x16x4_f32):
+//   F3  context[b] = P[b] . V[b]                 (Section 2, step 2)
+//   B1  dV[b] = P[b]^T . dC[b],  dP[b] = dC[b] . V[b]^T   (Eq. 2: only inputs needed)
+//   B2  dS = P (dP - rowsum(P dP)), fused behind dP so dP never leaves the CU
+//
+// Operand layout of one 16x16x4 step, lane l:  A[m = l%16][k = l/16],
+// B[k = l/16][n = l%16], D[m = 4*(l/16) + r][n = l%16] in accumulator r.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace echo {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ f32x4 mfma16(float a, float b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+// ---------------------------------------------------------------------------
+// out[b, m, n] = sum_k A(m, k) * Bm[b, k, n]
+//   TRANS_A = false: A(m, k) = P[b, m, k]   M = Tq, K = L_b   (context)
+//   TRANS_A = true : A(m, k) = P[b, k, m]   M = Tk, K = Tq    (dV; rows m >= L_b are zero)
+// A wave owns 16 rows x 64 columns: each lane loads four consecutive columns
+// of Bm (one 16-byte load) and feeds component c to column tile c, so the
+// output columns of tile c are n0 + 4*(l%16) + c and the store is 16 bytes too.
+// N must be a multiple of 4.
+template <typename TB, bool TRANS_A>
+__global__ __launch_bounds__(256) void k_pv(const float *__restrict__ P, const TB *__restrict__ Bm,
+                                            const int *__restrict__ key_len, float *__restrict__ out,
+                                            int Tq, int Tk, int N) {
+    const int b = blockIdx.z;
+    const int L = clamp_len(key_len[b], Tk);
+    const int lane = lane_id(), w = wave_id();
+    const int M = TRANS_A ? Tk : Tq;
+    const int K = TRANS_A ? Tq : L;
+    const int Mvalid = TRANS_A ? L : Tq;      // rows that can be non-zero
+    const int m0 = blockIdx.y * 16;
+    const int n0 = (blockIdx.x * 4 + w) * 64;
+    if (n0 >= N) return;
+    const int lm = lane & 15, lk = lane >> 4;
+    const int ncol = n0 + 4 * lm;             // first of this lane's four columns
+    const bool nok = ncol < N;
+    const float *Pb = P + (size_t)b * Tq * Tk;
+    const TB *Bb = Bm + (size_t)b * (TRANS_A ? Tq : Tk) * N;
+
+    f32x4 acc[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[c] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    if (m0 < Mvalid) {
+        const int m = m0 + lm;
+        for (int k0 = 0; k0 < K; k0 += 4) {
+            const int k = k0 + lk;
+            float a = 0.f;
+            if (m < Mvalid && k < K) a = TRANS_A ? Pb[(size_t)k * Tk + m] : Pb[(size_t)m * Tk + k];
+            float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k < K && nok) bv = ld4(Bb, (size_t)k * N + ncol);
+            acc[0] = mfma16(a, bv.x, acc[0]);
+            acc[1] = mfma16(a, bv.y, acc[1]);
+            acc[2] = mfma16(a, bv.z, acc[2]);
+            acc[3] = mfma16(a, bv.w, acc[3]);
+        }
+    }
+    if (!nok) return;
+    float *ob = out + (size_t)b * M * N;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int m = m0 + 4 * lk + r;
+        if (m < M) {
+            float4 o = make_float4(acc[0][r], acc[1][r], acc[2][r], acc[3][r]);
+            *reinterpret_cast<float4 *>(ob + (size_t)m * N + ncol) = o;
+        }
+    }
+}
+
+hipError_t launch_context(const AttnShape &s, const float *P, const void *V, const int *key_len, float *C,
+                          hipStream_t st) {
+    dim3 grid((s.Dv + 255) / 256, (s.Tq + 15) / 16, s.B);
+    if (s.bf16)
+        k_pv<bf16_t, false><<<grid, 256, 0, st>>>(P, (const bf16_t *)V, key_len, C, s.Tq, s.Tk, s.Dv);
+    else
+        k_pv<float, false><<<grid, 256, 0, st>>>(P, (const float *)V, key_len, C, s.Tq, s.Tk, s.Dv);
+    return hipGetLastError();
+}
+
+hipError_t launch_dvalue(const AttnShape &s, const float *P, const float *dC, const int *key_len, float *dV,
+                         hipStream_t st) {
+    dim3 grid((s.Dv + 255) / 256, (s.Tk + 15) / 16, s.B);
+    k_pv<float, true><<<grid, 256, 0, st>>>(P, dC, key_len, dV, s.Tq, s.Tk, s.Dv);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Block = (b, 16 query rows).  Waves take key tiles of 16 in turn and compute
+// dP[i, j] = sum_d dC[i, d] V[j, d] into LDS; then each wave finishes four
+// rows: r = sum_j P dP, dS = P (dP - r).  dS rows have pitch `pitch` floats and
+// are zero at j >= L_b (pads included).  Dv must be a multiple of 4.
+// A lane loads four consecutive d of its row for both operands and spends
+// them on four MFMA steps, so the k index of step c is d0 + 4*(l/16) + c on
+// both sides.
+template <typename TV>
+__global__ __launch_bounds__(256) void k_dscore(const float *__restrict__ dC, const TV *__restrict__ V,
+                                                const float *__restrict__ P, const int *__restrict__ key_len,
+                                                float *__restrict__ dS, float *__restrict__ ds_rowsum,
+                                                int Tq, int Tk, int Dv, int pitch) {
+    extern __shared__ float s_dp[];           // [16][pitch16]
+    const int b = blockIdx.y;
+    const int i0 = blockIdx.x * 16;
+    const int L = clamp_len(key_len[b], Tk);
+    const int lane = lane_id(), w = wave_id();
+    const int lm = lane & 15, lk = lane >> 4;
+    const int pitch16 = (Tk + 15) / 16 * 16 + 4;
+    const float *dCb = dC + (size_t)b * Tq * Dv;
+    const TV *Vb = V + (size_t)b * Tk * Dv;
+
+    const int n_jt = (L + 15) / 16;
+    for (int jt = w; jt < n_jt; jt += 4) {
+        const int i = i0 + lm, j = jt * 16 + lm;
+        const bool iok = i < Tq, jok = j < L;
+        f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int d0 = 0; d0 < Dv; d0 += 16) {
+            const int d = d0 + 4 * lk;
+            float4 a = make_float4(0.f, 0.f, 0.f, 0.f), bv = a;
+            if (d < Dv) {
+                if (iok) a = ld4(dCb, (size_t)i * Dv + d);
+                if (jok) bv = ld4(Vb, (size_t)j * Dv + d);
+            }
+            acc = mfma16(a.x, bv.x, acc);
+            acc = mfma16(a.y, bv.y, acc);
+            acc = mfma16(a.z, bv.z, acc);
+            acc = mfma16(a.w, bv.w, acc);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) s_dp[(4 * lk + r) * pitch16 + jt * 16 + lm] = acc[r];
+    }
+    __syncthreads();
+
+    for (int rr = w; rr < 16; rr += 4) {
+        const int i = i0 + rr;
+        if (i >= Tq) break;
+        const float *p = P + ((size_t)b * Tq + i) * Tk;
+        const float *dp = s_dp + rr * pitch16;
+        float *ds = dS + ((size_t)b * Tq + i) * pitch;
+        float r = 0.f;
+        for (int j = lane; j < L; j += 64) r += p[j] * dp[j];
+        r = wave_sum(r);
+        float tot = 0.f;
+        for (int j = lane; j < pitch; j += 64) {
+            float x = 0.f;
+            if (j < L) x = p[j] * (dp[j] - r);
+            ds[j] = x;
+            tot += x;
+        }
+        tot = wave_sum(tot);
+        if (lane == 0) ds_rowsum[(size_t)b * Tq + i] = tot;
+    }
+}
+
+hipError_t launch_dscore(const AttnShape &s, const float *dC, const void *V, const float *P, const int *key_len,
+                         float *dS, float *ds_rowsum, hipStream_t st) {
+    dim3 grid((s.Tq + 15) / 16, s.B);
+    const int pitch16 = (s.Tk + 15) / 16 * 16 + 4;
+    const size_t lds = (size_t)16 * pitch16 * sizeof(float);
+    if (lds > 48 * 1024) {   // beyond the default dynamic LDS limit: raise it (up to 160 KB per block on gfx950)
+        hipError_t e = s.bf16 ? hipFuncSetAttribute((const void *)k_dscore<bf16_t>,
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
+                              : hipFuncSetAttribute((const void *)k_dscore<float>,
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    if (s.bf16)
+        k_dscore<bf16_t><<<grid, 256, lds, st>>>(dC, (const bf16_t *)V, P, key_len, dS, ds_rowsum, s.Tq, s.Tk, s.Dv,
+                                                 ds_pitch(s.Tk));
+    else
+        k_dscore<float><<<grid, 256, lds, st>>>(dC, (const float *)V, P, key_len, dS, ds_rowsum, s.Tq, s.Tk, s.Dv,
+                                                ds_pitch(s.Tk));
+    return hipGetLastError();
+}
+
+}  // namespace echo

@@ -1,0 +1,43 @@
+// Host-side launch functions of the libechoattn kernels.  Each validates
+// nothing (the C ABI layer did) and returns hipGetLastError() after its launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+
+namespace echo {
+
+struct AttnShape {
+    int B, Tq, Tk, H, Dv;
+    bool bf16;   // Qp, Kp, V, v stored as bf16
+};
+
+// Row pitch (floats) of the dS workspace: keys rounded up to the key tile of
+// the recompute kernel, pad entries are written as zeros.
+constexpr int kDsPad = 8;
+inline int ds_pitch(int Tk) { return (Tk + kDsPad - 1) / kDsPad * kDsPad; }
+
+// F1  scores; tmap != nullptr also writes the tanh map (stash baseline)
+hipError_t launch_score(const AttnShape &s, const void *Qp, const void *Kp, const void *v, const int *key_len,
+                        float *S, float *tmap, hipStream_t st);
+// F2  masked softmax over keys, one wave per (b, i) row
+hipError_t launch_softmax(const AttnShape &s, const float *S, const int *key_len, float *P, hipStream_t st);
+// F3  context = P . V            (MFMA)
+hipError_t launch_context(const AttnShape &s, const float *P, const void *V, const int *key_len, float *C,
+                          hipStream_t st);
+// B1  dV = P^T . dC              (MFMA)
+hipError_t launch_dvalue(const AttnShape &s, const float *P, const float *dC, const int *key_len, float *dV,
+                         hipStream_t st);
+// B1+B2  dP = dC . V^T (MFMA) then dS = P (dP - rowsum(P dP)); dS has row pitch ds_pitch(Tk);
+// ds_rowsum[b*Tq+i] = sum_j dS
+hipError_t launch_dscore(const AttnShape &s, const float *dC, const void *V, const float *P, const int *key_len,
+                         float *dS, float *ds_rowsum, hipStream_t st);
+// B3  fused recompute: dQp, dKp, per-sample partials of dv  (dv_part [B,H]);
+// tmap != nullptr reads tanh from the stashed map instead of recomputing it
+hipError_t launch_recompute(const AttnShape &s, const void *Qp, const void *Kp, const void *v, const int *key_len,
+                            const float *dS, const float *tmap, float *dQp, float *dKp, float *dv_part,
+                            hipStream_t st);
+// B4  dv[h] = sum_b dv_part[b,h] + sum ds_rowsum, fixed order
+hipError_t launch_dv_reduce(const AttnShape &s, const float *dv_part, const float *ds_rowsum, float *dv,
+                            hipStream_t st);
+
+}  // namespace echo

@@ -1,0 +1,248 @@
+// B3: the fused recomputation kernel.  For every valid (b, i, j, h) it
+// re-evaluates t = tanh(Qp[b,i,h] + Kp[b,j,h]) (Section 3.4: redo the cheap
+// forward nodes when the backward pass starts; Section 6.1: the nodes on the
+// recomputation path fused into one kernel) and accumulates
+//     dQp[b,i,h] = v[h] sum_j dS[b,i,j] (1 - t^2)        (Section 3.2: tanh' = 1 - tanh^2)
+//     dKp[b,j,h] = v[h] sum_i dS[b,i,j] (1 - t^2)
+//     dv[h]     += sum_{i,j} dS[b,i,j] t                  (Eq. 2: needs the tanh map as the input of the v projection)
+// without the B x Tq x Tk x H map ever existing in memory.
+//
+// A block owns one sample and one 64-wide slice of h; lanes run along h, so
+// dS[b,i,j] is uniform over a wave and dQp, dKp, dv are plain per-lane sums.
+// With r = 1 / (exp(2(q+k)) + 1):  t = 1 - 2r  and  1 - t^2 = 4 r (1 - r).
+// Wave w owns query rows; all waves walk the keys together in tiles of RJ.
+// Per tile a wave adds its partial column sums into LDS, and after the
+// barrier wave jj sums key jj of the tile over the waves in fixed order and
+// owns that element of dKp for the whole kernel (first block of rows stores,
+// later ones add), so no atomics are needed and results are reproducible.
+//
+// STASH reads t from a stored map instead (the keep-the-feature-map baseline,
+// comparison only).
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace echo {
+
+constexpr int RC_RI = 8;      // query rows per wave and pass
+constexpr int RC_RJ = 8;      // keys per tile (== kDsPad)
+constexpr int RC_W = 8;       // waves per block (== RC_RJ: wave jj finishes key jj of a tile)
+constexpr int RC_THREADS = 64 * RC_W;
+static_assert(RC_RJ == kDsPad, "dS rows are padded to the key tile");
+static_assert(RC_W == RC_RJ, "one finishing wave per key of a tile");
+
+enum RcMode { RC_FACTOR = 0, RC_EXACT = 1, RC_STASH = 2 };
+
+// One RI x RJ register tile.  NI = number of live rows (compile time so the
+// accumulators stay in registers and the NI*RJ chains interleave freely).
+//   RC_FACTOR: fq = exp(2q), fk = exp(2k)        r = 1 / (fq fk + 1)
+//   RC_EXACT : fq = 2 log2e q, fk = 2 log2e k    r = 1 / (exp2(fq + fk) + 1)
+//   RC_STASH : t read from the stored map        r = (1 - t) / 2
+// ds_tile points at dS[b, i0, j0] (wave-uniform values, zero at masked keys);
+// t_tile at tmap[b, i0, 0, h] of this lane, kcol[c] = key index of column c
+// clamped into the valid range.
+template <int NI, int MODE>
+__device__ __forceinline__ void rc_tile(const float (&fq)[RC_RI], const float (&fk)[RC_RJ],
+                                        const float *__restrict__ ds_tile, int pitch,
+                                        const float *__restrict__ t_tile, size_t t_row, size_t t_key,
+                                        const int (&kcol)[RC_RJ],
+                                        float (&accQ)[RC_RI], float (&accK)[RC_RJ], float &accV) {
+#pragma unroll
+    for (int a = 0; a < NI; ++a) {
+#pragma unroll
+        for (int c = 0; c < RC_RJ; ++c) {
+            const float d = ds_tile[a * pitch + c];
+            float r;
+            if (MODE == RC_FACTOR) r = r_from_factors(fq[a], fk[c]);
+            else if (MODE == RC_EXACT) r = r_from_sum(fq[a], fk[c]);
+            else r = __builtin_fmaf(-0.5f, t_tile[a * t_row + kcol[c] * t_key], 0.5f);
+            const float u = __builtin_fmaf(-r, r, r);          // r (1 - r) = (1 - t^2) / 4
+            accQ[a] = __builtin_fmaf(d, u, accQ[a]);
+            accK[c] = __builtin_fmaf(d, u, accK[c]);
+            accV = __builtin_fmaf(d, r, accV);
+        }
+    }
+}
+
+template <int MODE>
+__device__ __forceinline__ void rc_tile_n(int ni, const float (&fq)[RC_RI], const float (&fk)[RC_RJ],
+                                          const float *__restrict__ ds_tile, int pitch,
+                                          const float *__restrict__ t_tile, size_t t_row, size_t t_key,
+                                          const int (&kcol)[RC_RJ],
+                                          float (&accQ)[RC_RI], float (&accK)[RC_RJ], float &accV) {
+#define RC_CASE(N) \
+    case N: rc_tile<N, MODE>(fq, fk, ds_tile, pitch, t_tile, t_row, t_key, kcol, accQ, accK, accV); break;
+    switch (ni) {
+        RC_CASE(1) RC_CASE(2) RC_CASE(3) RC_CASE(4) RC_CASE(5) RC_CASE(6) RC_CASE(7) RC_CASE(8)
+        default: break;
+    }
+#undef RC_CASE
+}
+
+template <typename T, bool STASH>
+__global__ __launch_bounds__(RC_THREADS) void k_recompute(
+    const T *__restrict__ Qp, const T *__restrict__ Kp, const T *__restrict__ v,
+    const int *__restrict__ key_len, const float *__restrict__ dS, const float *__restrict__ tmap,
+    float *__restrict__ dQp, float *__restrict__ dKp, float *__restrict__ dv_part,
+    int Tq, int Tk, int H, int pitch, int rows_per_pass) {
+    // Key tile staged once per block, double buffered: exp(2k) for the factor
+    // path, 2 log2e k for the exact path, and per key a flag "beyond the factor limit".
+    __shared__ float s_fk[2][RC_RJ][64];
+    __shared__ float s_sk[2][RC_RJ][64];
+    __shared__ int s_kbig[2][RC_RJ];
+    __shared__ float s_part[2][RC_W][RC_RJ][64];
+    __shared__ float s_dv[RC_W][64];
+
+    const int b = blockIdx.y;
+    const int lane = lane_id(), w = wave_id();
+    const int h = blockIdx.x * 64 + lane;
+    const bool hv = h < H;
+    const int hc = hv ? h : H - 1;
+    const int L = clamp_len(key_len[b], Tk);
+    const float vh = hv ? ld(v, hc) : 0.f;
+    const float v4 = 4.f * vh;
+
+    float *dQb = dQp + (size_t)b * Tq * H;
+    float *dKb = dKp + (size_t)b * Tk * H;
+
+    // masked keys: exact zeros
+    for (int j = L + w; j < Tk; j += RC_W)
+        if (hv) dKb[(size_t)j * H + h] = 0.f;
+    if (L == 0) {                                   // block-uniform
+        for (int i = w; i < Tq; i += RC_W)
+            if (hv) dQb[(size_t)i * H + h] = 0.f;
+        if (w == 0 && hv) dv_part[(size_t)b * H + h] = 0.f;
+        return;
+    }
+
+    const T *qb = Qp + (size_t)b * Tq * H;
+    const T *kb = Kp + (size_t)b * Tk * H;
+    const float *dsb = dS + (size_t)b * Tq * pitch;
+    const int n_jt = (L + RC_RJ - 1) / RC_RJ;
+    float accV = 0.f;
+
+    // wave w stages key w of a tile (RC_W == RC_RJ)
+    auto stage = [&](int jt, int buf) {
+        if (STASH) return;
+        const int j = jt * RC_RJ + w;
+        const float x = (j < L) ? ld(kb, (size_t)j * H + hc) : 0.f;
+        s_sk[buf][w][lane] = kTwoLog2e * x;
+        s_fk[buf][w][lane] = (j < L) ? fast_exp2(kTwoLog2e * x) : 0.f;
+        const int big = __any(fabsf(x) > kFactorLimit) ? 1 : 0;
+        if (lane == 0) s_kbig[buf][w] = big;
+    };
+
+    int pass = 0;
+    for (int i_pass0 = 0; i_pass0 < Tq; i_pass0 += rows_per_pass, ++pass) {
+        const int nrows = min(rows_per_pass, Tq - i_pass0);
+        const int r_lo = (nrows * w) / RC_W, r_hi = (nrows * (w + 1)) / RC_W;
+        const int ni = r_hi - r_lo;              // 0..RC_RI
+        const int i0 = i_pass0 + r_lo;
+
+        float fq[RC_RI], sq[RC_RI], accQ[RC_RI];
+        bool qbig = false;
+#pragma unroll
+        for (int a = 0; a < RC_RI; ++a) {
+            accQ[a] = 0.f;
+            float x = 0.f;
+            if (!STASH && a < ni) x = ld(qb, (size_t)(i0 + a) * H + hc);
+            qbig |= fabsf(x) > kFactorLimit;
+            sq[a] = kTwoLog2e * x;
+            fq[a] = fast_exp2(sq[a]);
+        }
+        const bool wave_qbig = __any(qbig);
+
+        stage(0, 0);
+        __syncthreads();
+
+        for (int jt = 0; jt < n_jt; ++jt) {
+            const int buf = jt & 1;
+            const int j0 = jt * RC_RJ;
+            float accK[RC_RJ], fk[RC_RJ];
+            int kcol[RC_RJ];
+#pragma unroll
+            for (int c = 0; c < RC_RJ; ++c) {
+                accK[c] = 0.f;
+                kcol[c] = min(j0 + c, L - 1);
+            }
+            const float *ds_tile = dsb + (size_t)i0 * pitch + j0;
+            if (STASH) {
+                const float *t_tile = tmap + (((size_t)b * Tq + i0) * Tk) * H + hc;
+#pragma unroll
+                for (int c = 0; c < RC_RJ; ++c) fk[c] = 0.f;
+                rc_tile_n<RC_STASH>(ni, fq, fk, ds_tile, pitch, t_tile, (size_t)Tk * H, (size_t)H, kcol, accQ, accK,
+                                    accV);
+            } else {
+                int kbig = 0;
+#pragma unroll
+                for (int c = 0; c < RC_RJ; ++c) kbig |= s_kbig[buf][c];
+                if (!(wave_qbig || kbig)) {
+#pragma unroll
+                    for (int c = 0; c < RC_RJ; ++c) fk[c] = s_fk[buf][c][lane];
+                    rc_tile_n<RC_FACTOR>(ni, fq, fk, ds_tile, pitch, nullptr, 0, 0, kcol, accQ, accK, accV);
+                } else {
+#pragma unroll
+                    for (int c = 0; c < RC_RJ; ++c) fk[c] = s_sk[buf][c][lane];
+                    rc_tile_n<RC_EXACT>(ni, sq, fk, ds_tile, pitch, nullptr, 0, 0, kcol, accQ, accK, accV);
+                }
+            }
+            if (jt + 1 < n_jt) stage(jt + 1, buf ^ 1);
+#pragma unroll
+            for (int c = 0; c < RC_RJ; ++c) s_part[buf][w][c][lane] = accK[c];
+            __syncthreads();
+            // wave w finishes key j0 + w of this tile: sum over the waves in fixed order
+            const int j = j0 + w;
+            float tot = 0.f;
+#pragma unroll
+            for (int w2 = 0; w2 < RC_W; ++w2) tot += s_part[buf][w2][w][lane];
+            if (j < L && hv) {
+                float *dst = dKb + (size_t)j * H + h;
+                const float val = v4 * tot;
+                *dst = (pass == 0) ? val : *dst + val;
+            }
+        }
+        if (hv) {
+#pragma unroll
+            for (int a = 0; a < RC_RI; ++a)
+                if (a < ni) dQb[(size_t)(i0 + a) * H + h] = v4 * accQ[a];
+        }
+        __syncthreads();   // the next pass restages buffer 0 and reuses s_part
+    }
+
+    // dv partial of this sample: sum dS t = sum dS - 2 sum dS r; the first term is added by the final reduction
+    s_dv[w][lane] = accV;
+    __syncthreads();
+    if (w == 0 && hv) {
+        float tot = 0.f;
+#pragma unroll
+        for (int w2 = 0; w2 < RC_W; ++w2) tot += s_dv[w2][lane];
+        dv_part[(size_t)b * H + h] = -2.f * tot;
+    }
+}
+
+template <typename T>
+static hipError_t launch_recompute_t(const AttnShape &s, const void *Qp, const void *Kp, const void *v,
+                                     const int *key_len, const float *dS, const float *tmap, float *dQp,
+                                     float *dKp, float *dv_part, hipStream_t st) {
+    const int max_rows = RC_W * RC_RI;
+    const int n_pass = (s.Tq + max_rows - 1) / max_rows;
+    const int rows_per_pass = (s.Tq + n_pass - 1) / n_pass;
+    dim3 grid((s.H + 63) / 64, s.B);
+    if (tmap)
+        k_recompute<T, true><<<grid, RC_THREADS, 0, st>>>((const T *)Qp, (const T *)Kp, (const T *)v, key_len, dS,
+                                                          tmap, dQp, dKp, dv_part, s.Tq, s.Tk, s.H,
+                                                          ds_pitch(s.Tk), rows_per_pass);
+    else
+        k_recompute<T, false><<<grid, RC_THREADS, 0, st>>>((const T *)Qp, (const T *)Kp, (const T *)v, key_len, dS,
+                                                           tmap, dQp, dKp, dv_part, s.Tq, s.Tk, s.H,
+                                                           ds_pitch(s.Tk), rows_per_pass);
+    return hipGetLastError();
+}
+
+hipError_t launch_recompute(const AttnShape &s, const void *Qp, const void *Kp, const void *v, const int *key_len,
+                            const float *dS, const float *tmap, float *dQp, float *dKp, float *dv_part,
+                            hipStream_t st) {
+    return s.bf16 ? launch_recompute_t<bf16_t>(s, Qp, Kp, v, key_len, dS, tmap, dQp, dKp, dv_part, st)
+                  : launch_recompute_t<float>(s, Qp, Kp, v, key_len, dS, tmap, dQp, dKp, dv_part, st);
+}
+
+}  // namespace echo

@@ -1,0 +1,60 @@
+// F2: masked softmax over the keys of one (b, i) row (attention weights,
+// Section 2 step 1), and B4: the fixed-order reduction that finishes dv.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace echo {
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+// One wave per row.  Keys j >= L_b get probability exactly 0; a row with no
+// valid key is all zeros.  The row maximum is subtracted before exponentiating.
+__global__ __launch_bounds__(256) void k_softmax(const float *__restrict__ S, const int *__restrict__ key_len,
+                                                 float *__restrict__ P, int rows, int Tq, int Tk) {
+    const int row = blockIdx.x * 4 + wave_id();
+    if (row >= rows) return;
+    const int lane = lane_id();
+    const int b = row / Tq;
+    const int L = clamp_len(key_len[b], Tk);
+    const float *s = S + (size_t)row * Tk;
+    float *p = P + (size_t)row * Tk;
+    float m = -INFINITY;
+    for (int j = lane; j < L; j += 64) m = fmaxf(m, s[j]);
+    m = wave_max(m);
+    float z = 0.f;
+    for (int j = lane; j < L; j += 64) z += fast_exp2((s[j] - m) * kLog2e);
+    z = wave_sum(z);
+    const float inv = 1.0f / z;
+    for (int j = lane; j < Tk; j += 64) p[j] = j < L ? fast_exp2((s[j] - m) * kLog2e) * inv : 0.f;
+}
+
+hipError_t launch_softmax(const AttnShape &s, const float *S, const int *key_len, float *P, hipStream_t st) {
+    const int rows = s.B * s.Tq;
+    k_softmax<<<(rows + 3) / 4, 256, 0, st>>>(S, key_len, P, rows, s.Tq, s.Tk);
+    return hipGetLastError();
+}
+
+// dv[h] = c0 + sum_b dv_part[b,h], b ascending; c0 = sum over all rows of
+// ds_rowsum (the part of sum dS*tanh that comes from tanh = 1 - 2r; it is zero
+// in exact arithmetic because every row of dS sums to zero).
+__global__ __launch_bounds__(64) void k_dv_reduce(const float *__restrict__ dv_part,
+                                                  const float *__restrict__ ds_rowsum, float *__restrict__ dv,
+                                                  int B, int rows, int H) {
+    const int lane = lane_id();
+    float c0 = 0.f;
+    for (int r = lane; r < rows; r += 64) c0 += ds_rowsum[r];
+    c0 = wave_sum(c0);
+    const int h = blockIdx.x * 64 + lane;
+    if (h >= H) return;
+    float acc = 0.f;
+    for (int b = 0; b < B; ++b) acc += dv_part[(size_t)b * H + h];
+    dv[h] = acc + c0;
+}
+
+hipError_t launch_dv_reduce(const AttnShape &s, const float *dv_part, const float *ds_rowsum, float *dv,
+                            hipStream_t st) {
+    k_dv_reduce<<<(s.H + 63) / 64, 64, 0, st>>>(dv_part, ds_rowsum, dv, s.B, s.B * s.Tq, s.H);
+    return hipGetLastError();
+}
+
+}  // namespace echo

@@ -1,0 +1,98 @@
+"""The C ABI without a GPU: the library loads, exports every symbol the header
+declares, and rejects bad arguments before any launch."""
+import os
+import re
+
+import pytest
+
+from paper_1805_08899_amd import binding as eb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "echoattn.h")
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(echo_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert "echo_attn_fwd" in names and "echo_attn_bwd" in names and len(names) >= 11
+    L = eb.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert set(names) == set(eb.EXPORTS), "binding and header disagree"
+
+
+def test_version_and_status_strings():
+    assert "gfx950" in eb.echo_version()
+    seen = {eb.echo_status_string(s) for s in range(7)}
+    assert len(seen) == 7 and "ok" in seen
+
+
+def test_workspace_queries():
+    d = eb.make_desc(64, 50, 50, 512, 512)
+    assert eb.echo_attn_fwd_workspace_bytes(d) >= 0
+    assert eb.echo_attn_bwd_workspace_bytes(d) >= 64 * 50 * 50 * 4
+    assert eb.echo_attn_stash_bytes(d) == 64 * 50 * 50 * 512 * 4
+    bad = eb.make_desc(0, 50, 50, 512, 512)
+    assert eb.echo_attn_fwd_workspace_bytes(bad) == 0 and eb.echo_attn_bwd_workspace_bytes(bad) == 0
+    assert eb.echo_attn_stash_bytes(bad) == 0
+
+
+A = 0x10000  # a fake, aligned, never dereferenced device address
+
+
+def _fwd(desc, **kw):
+    args = dict(Qp=A, Kp=A, V=A, v=A, key_len=A, context=A, P=A, workspace=A, workspace_bytes=1 << 40)
+    args.update(kw)
+    return eb.echo_attn_fwd(desc, **args)
+
+
+def _bwd(desc, **kw):
+    args = dict(dContext=A, P=A, Qp=A, Kp=A, V=A, v=A, key_len=A, dQp=A, dKp=A, dV=A, dv=A, workspace=A,
+                workspace_bytes=1 << 40)
+    args.update(kw)
+    return eb.echo_attn_bwd(desc, **args)
+
+
+def test_rejects_bad_arguments_without_launching():
+    good = eb.make_desc(4, 6, 7, 16, 16)
+    for name in ("Qp", "Kp", "V", "v", "key_len", "context", "P", "workspace"):
+        assert _fwd(good, **{name: None}) == eb.ECHO_ERR_NULL, name
+    for name in ("dContext", "P", "Qp", "Kp", "V", "v", "key_len", "dQp", "dKp", "dV", "dv", "workspace"):
+        assert _bwd(good, **{name: None}) == eb.ECHO_ERR_NULL, name
+    assert _fwd(good, Qp=A + 4) == eb.ECHO_ERR_ALIGN
+    assert _bwd(good, dKp=A + 8) == eb.ECHO_ERR_ALIGN
+    assert _fwd(good, workspace_bytes=eb.echo_attn_fwd_workspace_bytes(good) - 1) == eb.ECHO_ERR_WORKSPACE
+    assert _bwd(good, workspace_bytes=eb.echo_attn_bwd_workspace_bytes(good) - 1) == eb.ECHO_ERR_WORKSPACE
+    for field in ("B", "Tq", "Tk", "H", "Dv"):
+        for val in (0, -3):
+            d = eb.make_desc(4, 6, 7, 16, 16)
+            setattr(d, field, val)
+            assert _fwd(d) == eb.ECHO_ERR_SHAPE and _bwd(d) == eb.ECHO_ERR_SHAPE, (field, val)
+    assert _fwd(eb.make_desc(4, 6, 7, 16, 18)) == eb.ECHO_ERR_SHAPE          # Dv not a multiple of 4
+    assert _fwd(eb.make_desc(1, 70000, 70, 70000, 16)) == eb.ECHO_ERR_SHAPE  # per-sample tensor >= 2^31 elements
+    assert _fwd(eb.make_desc(4, 6, 7, 16, 16, in_dtype=7)) == eb.ECHO_ERR_DTYPE
+
+
+def test_null_descriptor():
+    import ctypes
+    L = eb.lib()
+    assert L.echo_attn_fwd(None, A, A, A, A, A, A, A, A, 1 << 40, None) == eb.ECHO_ERR_NULL
+    assert L.echo_attn_fwd_workspace_bytes(None) == 0
+
+
+def test_stash_entry_points_validate_too():
+    good = eb.make_desc(4, 6, 7, 16, 16)
+    assert eb.echo_attn_fwd_stash(good, A, A, A, A, A, A, A, None, A, 1 << 40) == eb.ECHO_ERR_NULL
+    assert eb.echo_attn_bwd_stash(good, A, A, None, A, A, A, A, A, A, A, A, 1 << 40) == eb.ECHO_ERR_NULL
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(eb, "_lib", None)
+    monkeypatch.setattr(eb, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(FileNotFoundError):
+        eb.lib()

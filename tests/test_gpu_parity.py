@@ -1,0 +1,124 @@
+"""HIP path against the float64 oracle, element by element, through the C ABI.
+
+Tolerance (stated by the benchmark spec): per output tensor max|gpu - ref| / max|ref|
+<= 1e-4 for fp32 inputs and <= 2e-2 for bf16-stored inputs; outputs at masked
+keys must be exact zeros.
+"""
+import numpy as np
+import pytest
+
+from paper_1805_08899_amd.workloads import WORKLOADS, Workload, make_inputs
+from parity import KEYS, assert_parity, oracle_outputs, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_1805_08899_amd import harness
+    return harness
+
+
+def run_gpu(H, wl, inputs, stash=False):
+    db = H.DeviceBatch(wl, inputs, stash=stash)
+    db.poison_outputs()
+    if stash:
+        db.fwd_stash(); db.bwd_stash()
+    else:
+        db.fwd(); db.bwd()
+    return db, db.results()
+
+
+@pytest.mark.parametrize("idx", [0, 1, 2, 3, 4])
+def test_workload_parity(H, idx):
+    wl = WORKLOADS[idx]
+    print(f"workload {wl.name}", flush=True)
+    inputs = make_inputs(wl)
+    db, got = run_gpu(H, wl, inputs)
+    ref = oracle_outputs(inputs, workers=1 if idx == 0 else None)
+    rep = assert_parity(got, ref, inputs, wl.in_dtype, wl.name)
+    print(wl.name, {k: f"{e:.2e}" for k, e in rep.items()}, flush=True)
+    # reproducible bit for bit
+    db.poison_outputs(); db.fwd(); db.bwd()
+    again = db.results()
+    for k in KEYS:
+        assert np.array_equal(got[k], again[k]), f"{k} differs between two runs"
+
+
+EDGE = [
+    # name, B, Tq, Tk, H, Dv, dtype, key_len (None = random 1..Tk)
+    ("single_query", 3, 1, 9, 40, 8, "f32", None),
+    ("single_key", 3, 5, 1, 33, 4, "f32", None),
+    ("h_equals_1", 2, 4, 5, 1, 4, "f32", None),
+    ("ragged_everything", 3, 37, 45, 200, 36, "f32", None),
+    ("h_not_multiple_of_64", 2, 19, 23, 70, 12, "f32", None),
+    ("empty_and_clamped_lengths", 5, 7, 12, 64, 16, "f32", [0, 12, 40, -3, 5]),
+    ("rows_in_several_passes", 2, 150, 21, 64, 8, "f32", None),
+    ("many_key_tiles", 1, 9, 1100, 64, 8, "f32", [1100]),
+    ("bf16_ragged", 3, 21, 34, 130, 20, "bf16", None),
+    ("bf16_empty_sample", 2, 6, 7, 16, 16, "bf16", [0, 7]),
+]
+
+
+@pytest.mark.parametrize("case", EDGE, ids=[c[0] for c in EDGE])
+def test_edge_shapes(H, case):
+    name, B, Tq, Tk, Hh, Dv, dt, kl = case
+    print("edge case", case, flush=True)
+    wl = Workload(name, B, Tq, Tk, Hh, Dv, dt, 0.5, 1, Tk, dt == "bf16")
+    inputs = make_inputs(wl, seed=1234 + len(name))
+    if kl is not None:
+        inputs["key_len"] = np.asarray(kl, dtype=np.int32)
+    _, got = run_gpu(H, wl, inputs)
+    ref = oracle_outputs(inputs, workers=1)
+    assert_parity(got, ref, inputs, dt, name)
+
+
+def test_large_preactivations_take_the_exact_path(H):
+    """|Qp + Kp| up to 100: tanh must saturate to +-1 with no NaN, and rows
+    beyond the factorisation limit must still be right next to ordinary rows."""
+    wl = Workload("saturating", 2, 10, 20, 96, 8, "f32", 0.5, 5, 20)
+    inputs = make_inputs(wl, seed=77)
+    inputs["Qp"][0, 3, :] = 60.0
+    inputs["Kp"][0, 2, :] = 40.0
+    inputs["Kp"][0, 4, :] = -59.5          # q + k = 0.5 with both far beyond the limit
+    inputs["Qp"][1, 7, 5:50] = -45.0
+    inputs["Kp"][1, 1, 10:60] = 44.0
+    inputs["key_len"][:] = [20, 9]
+    print("saturating case", flush=True)
+    _, got = run_gpu(H, wl, inputs)
+    ref = oracle_outputs(inputs, workers=1)
+    assert_parity(got, ref, inputs, "f32", "saturating")
+
+
+@pytest.mark.parametrize("idx", [0, 1])
+def test_stash_variant_matches(H, idx):
+    """The keep-the-feature-map baseline gives the same results, and its map
+    holds tanh(Qp + Kp) at the valid keys."""
+    wl = WORKLOADS[idx]
+    print("stash variant", wl.name, flush=True)
+    inputs = make_inputs(wl)
+    db, got = run_gpu(H, wl, inputs, stash=True)
+    ref = oracle_outputs(inputs, workers=1 if idx == 0 else None)
+    assert_parity(got, ref, inputs, wl.in_dtype, wl.name + " (stash)")
+    tm = db.tanh_map.view(wl.B, wl.Tq, wl.Tk, wl.H)
+    for b in (0, wl.B - 1):
+        L = int(inputs["key_len"][b])
+        want = np.tanh(inputs["Qp"][b].astype(np.float64)[:, None, :] + inputs["Kp"][b, :L].astype(np.float64)[None])
+        assert np.abs(tm[b, :, :L].cpu().numpy() - want).max() < 5e-7
+
+
+def test_forward_only_and_backward_from_given_P(H):
+    """The backward call must use the P it is handed (here: the oracle's)."""
+    import torch
+    wl = WORKLOADS[0]
+    inputs = make_inputs(wl, seed=5)
+    ref = oracle_outputs(inputs, workers=1)
+    db = H.DeviceBatch(wl, inputs)
+    db.poison_outputs()
+    db.P.copy_(torch.from_numpy(ref["P"].astype(np.float32)))
+    db.bwd()
+    got = db.results()
+    for k in ("dQp", "dKp", "dV", "dv"):
+        assert rel_err(got[k], ref[k]) <= 1e-4, k
