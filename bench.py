@@ -1,0 +1,252 @@
+#!/usr/bin/env python3
+"""Benchmark of the additive-attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1] [--no-cpu-baseline]
+
+One step = echo_attn_fwd followed by echo_attn_bwd over one resident batch of
+the chosen workload (default: workload 1, B=64, Tq=Tk=50, H=Dv=512, fp32).
+Prints ONE JSON line: whole-job fwd+bwd calls/s, the roofline of the dominant
+kernel (timed live with HIP events on the launch stream), the measured machine
+ceilings, peak device bytes beside the keep-the-feature-map variant, and the
+float64 oracle timed on the host cores as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X: 256 CUs x 4 SIMDs x 16 fp32 lanes at 2.4 GHz -> vector instruction
+# issue slots per second (one slot = one fp32 lane-operation, FMA counts once).
+PEAK_LANEOPS = 256 * 4 * 16 * 2.4e9          # 39.3e12
+PEAK_HBM = 8.0e12
+# Issue-slot cost per tanh evaluation of the two hot loops as written
+# (transcendentals issue at a quarter of the fp32 rate):
+#   score loop     fma, rcp, fma            -> 2 + 4 = 6 slots
+#   recompute loop fma, rcp, 4 fma          -> 5 + 4 = 9 slots
+# and of the textbook form 1 exp + 1 rcp + full-rate ops: 13 and 18 slots.
+SLOTS_ISSUED = {"score": 6.0, "recompute": 9.0}
+SLOTS_CANONICAL = {"score": 13.0, "recompute": 18.0}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stash", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (a batch shards over samples, "
+              "see DESIGN.md, but no multi-GPU path is built)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_1805_08899_amd import binding as eb
+    from paper_1805_08899_amd import footprint, harness
+    from paper_1805_08899_amd.workloads import WORKLOADS, make_inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    eb.lib()   # fails loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.init()
+    torch.empty(1, device=dev)
+    wl = WORKLOADS[args.workload]
+    inputs = make_inputs(wl)
+    L = np.clip(inputs["key_len"], 0, wl.Tk).astype(np.int64)
+    n4u = int(wl.Tq * wl.H * L.sum())           # unmasked (b,i,j,h) elements = tanh evaluations per pass
+
+    torch.cuda.reset_peak_memory_stats(dev)
+    base_alloc = torch.cuda.memory_allocated(dev)
+    db = harness.DeviceBatch(wl, inputs, device=dev)
+
+    def step():
+        db.fwd()
+        db.bwd()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize(dev)
+    peak_recompute = torch.cuda.max_memory_allocated(dev) - base_alloc
+
+    # ---- timed region: exactly K steps, inputs resident
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize(dev)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize(dev)
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    ms_per_step_events = ev0.elapsed_time(ev1) / args.steps
+
+    def time_only(fn, n):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize(dev)
+        a.record()
+        for _ in range(n):
+            fn()
+        b.record()
+        torch.cuda.synchronize(dev)
+        return a.elapsed_time(b) / n
+
+    fwd_ms = time_only(db.fwd, args.steps)
+    bwd_ms = time_only(db.bwd, args.steps)
+
+    # ---- per-kernel durations, HIP events on the launch stream
+    eb.echo_attn_profile_enable(True)
+    nprof = min(args.steps, 50)
+    for _ in range(nprof):
+        step()
+    prof = eb.echo_attn_profile_read()
+    eb.echo_attn_profile_enable(False)
+    kernels = {k: {"launches": n, "avg_us": 1e3 * ms / n} for k, (n, ms) in prof.items()}
+    dominant = max(kernels, key=lambda k: kernels[k]["avg_us"] * kernels[k]["launches"])
+
+    # ---- machine ceilings measured here
+    cal = calibrate(eb, torch, dev)
+
+    dom_us = kernels[dominant]["avg_us"]
+    if dominant in SLOTS_ISSUED:
+        slots = SLOTS_ISSUED[dominant] * n4u
+        achieved = slots / (dom_us * 1e-6)
+        mix = cal["fwd_mix_tanh_per_s"] if dominant == "score" else cal["bwd_mix_tanh_per_s"]
+        roofline = {
+            "kernel": dominant, "bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_LANEOPS / 1e12,
+            "unit": "Tlaneop/s", "frac": achieved / PEAK_LANEOPS, "traffic": None,
+            "avg_launch_us": dom_us, "tanh_evals_per_launch": n4u,
+            "slots_per_tanh_issued": SLOTS_ISSUED[dominant],
+            "frac_canonical_form": SLOTS_CANONICAL[dominant] * n4u / (dom_us * 1e-6) / PEAK_LANEOPS,
+            "frac_of_measured_mix_ceiling": (n4u / (dom_us * 1e-6)) / mix if mix else None,
+        }
+    else:
+        roofline = {"kernel": dominant, "bound": "hbm", "achieved": None, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                    "frac": None, "traffic": None, "avg_launch_us": dom_us}
+
+    # end-to-end roofline time: arithmetic slots of both hot loops against the HBM minimum
+    s_in = 2 if wl.in_dtype == "bf16" else 4
+    io_bytes = ((wl.B * wl.Tq * wl.H + wl.B * wl.Tk * wl.H + wl.B * wl.Tk * wl.Dv) * s_in * 2   # fwd + bwd reads
+                + 4 * (wl.B * wl.Tq * wl.Dv * 2 + wl.B * wl.Tq * wl.Tk * 2)                      # C, dC, P w+r
+                + 4 * (wl.B * wl.Tq * wl.H + wl.B * wl.Tk * wl.H + wl.B * wl.Tk * wl.Dv))         # dQp, dKp, dV
+    t_alu = (SLOTS_ISSUED["score"] + SLOTS_ISSUED["recompute"]) * n4u / PEAK_LANEOPS
+    t_hbm = io_bytes / PEAK_HBM
+    end_to_end = {"t_alu_us": t_alu * 1e6, "t_hbm_us": t_hbm * 1e6, "io_bytes": io_bytes,
+                  "frac": max(t_alu, t_hbm) / (ms_per_step_events * 1e-3)}
+
+    # ---- peak bytes next to the variant that keeps the 4-D tanh map
+    fp_rec = footprint.footprint(wl.B, wl.Tq, wl.Tk, wl.H, wl.Dv, wl.in_dtype, stash=False,
+                                 fwd_ws=db.fwd_ws_bytes, bwd_ws=db.bwd_ws_bytes)
+    fp_stash = footprint.footprint(wl.B, wl.Tq, wl.Tk, wl.H, wl.Dv, wl.in_dtype, stash=True,
+                                   fwd_ws=db.fwd_ws_bytes, bwd_ws=db.bwd_ws_bytes)
+    peak = {"recompute_measured": int(peak_recompute), "recompute_analytic": fp_rec.total,
+            "stash_analytic": fp_stash.total, "tanh_map_bytes": wl.n4 * 4}
+    stash_timing = None
+    if not args.no_stash and wl.n4 * 4 <= 16 << 30:
+        del db
+        torch.cuda.empty_cache()
+        torch.cuda.reset_peak_memory_stats(dev)
+        base2 = torch.cuda.memory_allocated(dev)
+        dbs = harness.DeviceBatch(wl, inputs, device=dev, stash=True)
+        for _ in range(3):
+            dbs.fwd_stash(); dbs.bwd_stash()
+        torch.cuda.synchronize(dev)
+        peak["stash_measured"] = int(torch.cuda.max_memory_allocated(dev) - base2)
+        n = max(5, min(args.steps, 20))
+        stash_timing = {"fwd_ms": time_only(dbs.fwd_stash, n), "bwd_ms": time_only(dbs.bwd_stash, n)}
+        del dbs
+        torch.cuda.empty_cache()
+
+    cpu = None if args.no_cpu_baseline else cpu_baseline(wl, inputs)
+
+    out = {
+        "metric": "attention fwd+bwd calls/s",
+        "value": args.steps / wall,
+        "unit": "calls/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if wl.in_dtype == "f32" else "bf16 storage, f32 arithmetic",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "B": wl.B, "Tq": wl.Tq, "Tk": wl.Tk, "H": wl.H, "Dv": wl.Dv,
+                   "in_dtype": wl.in_dtype, "mean_key_len": float(L.mean())},
+        "ms_per_step_events": ms_per_step_events, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
+        "kernels": kernels,
+        "roofline": roofline,
+        "end_to_end_roofline": end_to_end,
+        "measured_ceilings": cal,
+        "peak_bytes": peak,
+        "stash_variant_ms": stash_timing,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+def calibrate(eb, torch, dev):
+    """Times the synthetic kernels of echo_attn_calibrate with events."""
+    blocks, iters = 256 * 16, 256
+    scratch = torch.empty(blocks * 256, dtype=torch.float32, device=dev)
+    st = torch.cuda.current_stream(dev)
+
+    def run(kind, src=None, dst=scratch, nbytes=None, reps=3):
+        nbytes = dst.numel() * 4 if nbytes is None else nbytes
+        best = None
+        for _ in range(reps + 1):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            rc, work = eb.echo_attn_calibrate(kind, blocks, iters, src, dst, nbytes, stream=st)
+            b.record()
+            eb.check(rc, "echo_attn_calibrate")
+            torch.cuda.synchronize(dev)
+            rate = work / (a.elapsed_time(b) * 1e-3)
+            best = rate if best is None else max(best, rate)
+        return best
+
+    out = {
+        "fma_laneops_per_s": run(eb.ECHO_CAL_FMA),
+        "rcp_laneops_per_s": run(eb.ECHO_CAL_RCP),
+        "exp2_laneops_per_s": run(eb.ECHO_CAL_EXP2),
+        "fwd_mix_tanh_per_s": run(eb.ECHO_CAL_FWD_MIX),
+        "bwd_mix_tanh_per_s": run(eb.ECHO_CAL_BWD_MIX),
+    }
+    n = 1 << 28   # 256 MiB each way
+    src = torch.empty(n, dtype=torch.uint8, device=dev)
+    dst = torch.empty(n, dtype=torch.uint8, device=dev)
+    out["copy_read_plus_write_bytes_per_s"] = 2 * run(eb.ECHO_CAL_COPY, src=src, dst=dst, nbytes=n)
+    return out
+
+
+def cpu_baseline(wl, inputs):
+    """The float64 oracle, as it stands, on the host cores of this machine."""
+    import numpy as np
+    from oracle import parallel
+    cores = parallel.usable_cores()
+    # bounded sample: whole batch while it is cheap, else as many samples as there are cores
+    per_sample = wl.Tq * wl.Tk * wl.H
+    nb = wl.B if per_sample * wl.B <= 2e8 else min(wl.B, cores)
+    sl = slice(0, nb)
+    t0 = time.perf_counter()
+    parallel.forward_backward(inputs["Qp"][sl], inputs["Kp"][sl], inputs["V"][sl], inputs["v"],
+                              inputs["key_len"][sl], inputs["dContext"][sl], workers=cores)
+    dt = time.perf_counter() - t0
+    frac = float(np.clip(inputs["key_len"][sl], 0, wl.Tk).sum() / np.clip(inputs["key_len"], 0, wl.Tk).sum())
+    return {"value": frac / dt, "unit": "calls/s", "cores": min(cores, nb), "kind": "oracle",
+            "sample": f"{nb} of {wl.B} samples of {wl.name}, one fwd+bwd in float64, {dt:.2f} s wall; "
+                      f"scaled to a whole call by the share of unmasked keys ({frac:.3f})"}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

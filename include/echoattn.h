@@ -127,6 +127,23 @@ echo_status_t echo_attn_bwd_stash(const echo_attn_desc_t *desc,
 void echo_attn_profile_enable(int on);
 int  echo_attn_profile_read(const char **names, int *launches, float *total_ms, int cap);
 
+/* Measurement support: launches one synthetic kernel on `stream` so that the
+ * caller can time the machine's ceilings with its own events.
+ *   ECHO_CAL_FMA / RCP / EXP2   every lane issues nothing but v_fma_f32 /
+ *                               v_rcp_f32 / v_exp_f32 in 16 independent chains
+ *   ECHO_CAL_FWD_MIX            the per-tanh instruction mix of the score loop
+ *                               (fma, rcp, fma); *work counts tanh evaluations
+ *   ECHO_CAL_BWD_MIX            the mix of the recompute loop (fma, rcp, 4 fma)
+ *   ECHO_CAL_COPY               dst[i] = src[i] over `bytes` bytes (16-byte units)
+ * ALU kinds launch `blocks` blocks of 256 lanes, each running `iters` loop
+ * trips, and write one float per lane to dst (bytes >= blocks*256*4).
+ * *work (HOST) receives the number of lane-instructions (FMA/RCP/EXP2), of
+ * tanh-equivalents (mixes) or of bytes copied (COPY; read + write is twice that). */
+typedef enum { ECHO_CAL_FMA = 0, ECHO_CAL_RCP = 1, ECHO_CAL_EXP2 = 2, ECHO_CAL_FWD_MIX = 3,
+               ECHO_CAL_BWD_MIX = 4, ECHO_CAL_COPY = 5 } echo_cal_kind_t;
+echo_status_t echo_attn_calibrate(int kind, int blocks, int iters, const void *src, void *dst, size_t bytes,
+                                  double *work, void *stream);
+
 const char *echo_status_string(echo_status_t s);
 const char *echo_version(void);
 

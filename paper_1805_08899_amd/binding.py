@@ -41,6 +41,8 @@ EXPORTS = {
     "echo_attn_bwd_stash": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 11 + [c_size_t, c_void_p]),
     "echo_attn_profile_enable": (None, [c_int]),
     "echo_attn_profile_read": (c_int, [POINTER(c_char_p), POINTER(c_int), POINTER(c_float), c_int]),
+    "echo_attn_calibrate": (c_int, [c_int, c_int, c_int, c_void_p, c_void_p, c_size_t, POINTER(ctypes.c_double),
+                                    c_void_p]),
     "echo_status_string": (c_char_p, [c_int]),
     "echo_version": (c_char_p, []),
 }
@@ -144,6 +146,17 @@ def echo_attn_profile_read(cap: int = 32):
     ms = (c_float * cap)()
     n = min(lib().echo_attn_profile_read(names, launches, ms, cap), cap)
     return {names[i].decode(): (launches[i], ms[i]) for i in range(n)}
+
+
+ECHO_CAL_FMA, ECHO_CAL_RCP, ECHO_CAL_EXP2, ECHO_CAL_FWD_MIX, ECHO_CAL_BWD_MIX, ECHO_CAL_COPY = range(6)
+
+
+def echo_attn_calibrate(kind, blocks, iters, src, dst, nbytes, stream=None):
+    """Returns (status, work) -- see the header for the meaning of `work`."""
+    work = ctypes.c_double(0.0)
+    st = lib().echo_attn_calibrate(kind, blocks, iters, _ptr(src), _ptr(dst), nbytes, ctypes.byref(work),
+                                   _stream(stream))
+    return st, work.value
 
 
 def echo_status_string(status: int) -> str:
