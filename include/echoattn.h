@@ -145,6 +145,8 @@ echo_status_t echo_attn_calibrate(int kind, int blocks, int iters, const void *s
                                   double *work, void *stream);
 
 const char *echo_status_string(echo_status_t s);
+/* Kernel name and HIP error text of the calling thread's last ECHO_ERR_HIP ("" if none). */
+const char *echo_last_error_detail(void);
 const char *echo_version(void);
 
 #ifdef __cplusplus

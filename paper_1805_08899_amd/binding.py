@@ -27,7 +27,8 @@ class echo_attn_desc_t(ctypes.Structure):
 class EchoError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__(f"{where}: {echo_status_string(status)} (status {status})")
+        detail = echo_last_error_detail() if status == ECHO_ERR_HIP else ""
+        super().__init__(f"{where}: {echo_status_string(status)} (status {status}) {detail}")
 
 
 EXPORTS = {
@@ -44,6 +45,7 @@ EXPORTS = {
     "echo_attn_calibrate": (c_int, [c_int, c_int, c_int, c_void_p, c_void_p, c_size_t, POINTER(ctypes.c_double),
                                     c_void_p]),
     "echo_status_string": (c_char_p, [c_int]),
+    "echo_last_error_detail": (c_char_p, []),
     "echo_version": (c_char_p, []),
 }
 
@@ -161,6 +163,10 @@ def echo_attn_calibrate(kind, blocks, iters, src, dst, nbytes, stream=None):
 
 def echo_status_string(status: int) -> str:
     return lib().echo_status_string(int(status)).decode()
+
+
+def echo_last_error_detail() -> str:
+    return lib().echo_last_error_detail().decode()
 
 
 def echo_version() -> str:

@@ -39,14 +39,15 @@ echo_status_t check_desc(const echo_attn_desc_t *d, AttnShape *s) {
 inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 struct BwdWs {
-    size_t ds_off, rowsum_off, dvpart_off, total;
+    size_t ds_off, rowsum_off, dvpart_off, order_off, total;
 };
 BwdWs bwd_layout(const AttnShape &s) {
     BwdWs w;
     w.ds_off = 0;
     w.rowsum_off = align_up((size_t)s.B * s.Tq * echo::ds_pitch(s.Tk) * sizeof(float));
     w.dvpart_off = w.rowsum_off + align_up((size_t)s.B * s.Tq * sizeof(float));
-    w.total = w.dvpart_off + align_up((size_t)s.B * s.H * sizeof(float));
+    w.order_off = w.dvpart_off + align_up((size_t)s.B * s.H * sizeof(float));
+    w.total = w.order_off + align_up((size_t)s.B * sizeof(int));
     return w;
 }
 size_t fwd_bytes(const AttnShape &s) { return align_up((size_t)s.B * s.Tq * s.Tk * sizeof(float)); }
@@ -75,14 +76,19 @@ struct Timed {
     }
 };
 
-#define ECHO_LAUNCH(NAME, CALL)                    \
-    do {                                           \
-        hipError_t e_;                             \
-        {                                          \
-            Timed t_(NAME, st);                    \
-            e_ = (CALL);                           \
-        }                                          \
-        if (e_ != hipSuccess) return ECHO_ERR_HIP; \
+thread_local std::string g_last_error;
+
+#define ECHO_LAUNCH(NAME, CALL)                                                  \
+    do {                                                                         \
+        hipError_t e_;                                                           \
+        {                                                                        \
+            Timed t_(NAME, st);                                                  \
+            e_ = (CALL);                                                         \
+        }                                                                        \
+        if (e_ != hipSuccess) {                                                  \
+            g_last_error = std::string(NAME) + ": " + hipGetErrorString(e_);     \
+            return ECHO_ERR_HIP;                                                 \
+        }                                                                        \
     } while (0)
 
 echo_status_t fwd_impl(const echo_attn_desc_t *desc, const void *Qp, const void *Kp, const void *V, const void *v,
@@ -99,6 +105,10 @@ echo_status_t fwd_impl(const echo_attn_desc_t *desc, const void *Qp, const void 
     if (workspace_bytes < fwd_bytes(s)) return ECHO_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     float *S = static_cast<float *>(workspace);
+    if (!want_map && echo::fwd_fused_lds_bytes(s) <= 150 * 1024 && (size_t)s.B * sizeof(int) <= 64 * 1024) {
+        ECHO_LAUNCH("fwd_fused", echo::launch_fwd_fused(s, Qp, Kp, V, v, key_len, context, P, st));
+        return ECHO_OK;
+    }
     ECHO_LAUNCH(want_map ? "score_stash" : "score",
                 echo::launch_score(s, Qp, Kp, v, key_len, S, want_map ? tmap : nullptr, st));
     ECHO_LAUNCH("softmax", echo::launch_softmax(s, S, key_len, P, st));
@@ -125,10 +135,12 @@ echo_status_t bwd_impl(const echo_attn_desc_t *desc, const float *dContext, cons
     float *dS = reinterpret_cast<float *>(ws + lay.ds_off);
     float *rowsum = reinterpret_cast<float *>(ws + lay.rowsum_off);
     float *dv_part = reinterpret_cast<float *>(ws + lay.dvpart_off);
+    int *order = reinterpret_cast<int *>(ws + lay.order_off);
     ECHO_LAUNCH("dvalue", echo::launch_dvalue(s, P, dContext, key_len, dV, st));
-    ECHO_LAUNCH("dscore", echo::launch_dscore(s, dContext, V, P, key_len, dS, rowsum, st));
+    ECHO_LAUNCH("dscore", echo::launch_dscore(s, dContext, V, P, key_len, dS, rowsum, order, st));
     ECHO_LAUNCH(use_map ? "recompute_stash" : "recompute",
-                echo::launch_recompute(s, Qp, Kp, v, key_len, dS, use_map ? tmap : nullptr, dQp, dKp, dv_part, st));
+                echo::launch_recompute(s, Qp, Kp, v, key_len, order, dS, use_map ? tmap : nullptr, dQp, dKp, dv_part,
+                                       st));
     ECHO_LAUNCH("dv_reduce", echo::launch_dv_reduce(s, dv_part, rowsum, dv, st));
     return ECHO_OK;
 }
@@ -231,6 +243,8 @@ const char *echo_status_string(echo_status_t s) {
     }
     return "unknown status";
 }
+
+const char *echo_last_error_detail(void) { return g_last_error.c_str(); }
 
 const char *echo_version(void) { return "libechoattn 0.1 (gfx950)"; }
 

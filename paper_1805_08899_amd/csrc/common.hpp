@@ -66,29 +66,53 @@ __device__ __forceinline__ float wave_max(float x) {
     return x;
 }
 
+// ---------------------------------------------------------------------------
 // Sum N per-lane arrays over the 64 lanes of a wave at a cost of about one
-// exchange per value instead of six: at each butterfly level a lane keeps one
-// half of its values and hands the other half to its partner.  On return lane
-// l holds in a[0] the full sum of value number (l mod N).  N is a power of two
-// <= 64; the order of additions is fixed.
+// exchange per value instead of six.  At each level a lane keeps one half of
+// its values and hands the other half to the partner lane `OFF` away (levels
+// 32 and 16 with the gfx950 lane-swap instructions, 8 and 4 with DPP row
+// shifts selected by bank masks); once one value is left the remaining levels
+// are plain butterflies.  On return lane l holds in a[0] the full sum of value
+// number l / (64 / N).  N is a power of two <= 64; the order of additions is fixed.
+template <int CTRL, int BANK_MASK, bool BOUND>
+__device__ __forceinline__ float dpp_mov(float old, float src) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(src), CTRL, 0xf, BANK_MASK, BOUND));
+}
+
+// x = value kept by lanes whose bit OFF is 0, y = value kept by the others.
+template <int OFF>
+__device__ __forceinline__ float transpose_pair(float x, float y, int lane) {
+    if constexpr (OFF == 32) {
+        auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(y), false, false);
+        return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    } else if constexpr (OFF == 16) {
+        auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(y), false, false);
+        return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    } else if constexpr (OFF == 8 || OFF == 4) {
+        constexpr int SHL = 0x100 + OFF, SHR = 0x110 + OFF;     // row_shl:OFF / row_shr:OFF
+        constexpr int LO_BANKS = OFF == 8 ? 0x3 : 0x5;           // lanes of a row whose bit OFF is 0
+        const float t_lo = x + dpp_mov<SHL, 0xf, true>(0.f, x);  // x[l] + x[l + OFF]   (right where bit OFF is 0)
+        const float t_hi = y + dpp_mov<SHR, 0xf, true>(0.f, y);  // y[l] + y[l - OFF]   (right where bit OFF is 1)
+        return dpp_mov<0xE4, LO_BANKS, false>(t_hi, t_lo);       // identity move into the low banks only
+    } else {
+        const bool hi = (lane & OFF) != 0;
+        const float keep = hi ? y : x;
+        const float send = hi ? x : y;
+        return keep + __shfl_xor(send, OFF, 64);
+    }
+}
+
 template <int N, int OFF>
 struct TransposeSumStep {
-    // N values are still spread over lanes whose index differs in bit OFF and below
     template <int M>
     static __device__ __forceinline__ void run(float (&a)[M], int lane) {
-        if constexpr (OFF >= N) {   // more lanes than values left to split: plain butterfly
-#pragma unroll
-            for (int k = 0; k < N; ++k) a[k] += __shfl_xor(a[k], OFF, 64);
-            if constexpr (OFF > 1) TransposeSumStep<N, OFF / 2>::run(a, lane);
+        if constexpr (N == 1) {      // one value left: plain butterfly over the remaining lane bits
+            a[0] += __shfl_xor(a[0], OFF, 64);
+            if constexpr (OFF > 1) TransposeSumStep<1, OFF / 2>::run(a, lane);
         } else {
-            const bool hi = (lane & OFF) != 0;
             constexpr int half = N / 2;
 #pragma unroll
-            for (int k = 0; k < half; ++k) {
-                const float keep = hi ? a[k + half] : a[k];
-                const float send = hi ? a[k] : a[k + half];
-                a[k] = keep + __shfl_xor(send, OFF, 64);
-            }
+            for (int k = 0; k < half; ++k) a[k] = transpose_pair<OFF>(a[k], a[k + half], lane);
             if constexpr (OFF > 1) TransposeSumStep<half, OFF / 2>::run(a, lane);
         }
     }

@@ -103,9 +103,25 @@ template <typename TV>
 __global__ __launch_bounds__(256) void k_dscore(const float *__restrict__ dC, const TV *__restrict__ V,
                                                 const float *__restrict__ P, const int *__restrict__ key_len,
                                                 float *__restrict__ dS, float *__restrict__ ds_rowsum,
+                                                int *__restrict__ order, int B, int sorted,
                                                 int Tq, int Tk, int Dv, int pitch) {
     extern __shared__ float s_dp[];           // [16][pitch16]
     const int b = blockIdx.y;
+    if (order && blockIdx.x == 0 && blockIdx.y == 0) {
+        // for the recompute kernel: samples ordered by valid keys, most first (ties by index)
+        for (int cand = threadIdx.x; cand < B; cand += 256) {
+            int r = cand;
+            if (sorted) {
+                const int lc = clamp_len(key_len[cand], Tk);
+                r = 0;
+                for (int o = 0; o < B; ++o) {
+                    const int lo = clamp_len(key_len[o], Tk);
+                    r += (lo > lc) || (lo == lc && o < cand);
+                }
+            }
+            order[r] = cand;
+        }
+    }
     const int i0 = blockIdx.x * 16;
     const int L = clamp_len(key_len[b], Tk);
     const int lane = lane_id(), w = wave_id();
@@ -158,7 +174,8 @@ __global__ __launch_bounds__(256) void k_dscore(const float *__restrict__ dC, co
 }
 
 hipError_t launch_dscore(const AttnShape &s, const float *dC, const void *V, const float *P, const int *key_len,
-                         float *dS, float *ds_rowsum, hipStream_t st) {
+                         float *dS, float *ds_rowsum, int *order, hipStream_t st) {
+    const int sorted = s.B <= kMaxSortedB ? 1 : 0;
     dim3 grid((s.Tq + 15) / 16, s.B);
     const int pitch16 = (s.Tk + 15) / 16 * 16 + 4;
     const size_t lds = (size_t)16 * pitch16 * sizeof(float);
@@ -170,11 +187,11 @@ hipError_t launch_dscore(const AttnShape &s, const float *dC, const void *V, con
         if (e != hipSuccess) return e;
     }
     if (s.bf16)
-        k_dscore<bf16_t><<<grid, 256, lds, st>>>(dC, (const bf16_t *)V, P, key_len, dS, ds_rowsum, s.Tq, s.Tk, s.Dv,
-                                                 ds_pitch(s.Tk));
+        k_dscore<bf16_t><<<grid, 256, lds, st>>>(dC, (const bf16_t *)V, P, key_len, dS, ds_rowsum, order, s.B, sorted,
+                                                 s.Tq, s.Tk, s.Dv, ds_pitch(s.Tk));
     else
-        k_dscore<float><<<grid, 256, lds, st>>>(dC, (const float *)V, P, key_len, dS, ds_rowsum, s.Tq, s.Tk, s.Dv,
-                                                ds_pitch(s.Tk));
+        k_dscore<float><<<grid, 256, lds, st>>>(dC, (const float *)V, P, key_len, dS, ds_rowsum, order, s.B, sorted,
+                                                s.Tq, s.Tk, s.Dv, ds_pitch(s.Tk));
     return hipGetLastError();
 }
 

@@ -19,6 +19,10 @@ inline int ds_pitch(int Tk) { return (Tk + kDsPad - 1) / kDsPad * kDsPad; }
 // F1  scores; tmap != nullptr also writes the tanh map (stash baseline)
 hipError_t launch_score(const AttnShape &s, const void *Qp, const void *Kp, const void *v, const int *key_len,
                         float *S, float *tmap, hipStream_t st);
+// F1+F2+F3 in one kernel (no workspace); needs fwd_fused_lds_bytes(s) <= 160 KB of LDS and B <= 2048 for the ranking
+size_t fwd_fused_lds_bytes(const AttnShape &s);
+hipError_t launch_fwd_fused(const AttnShape &s, const void *Qp, const void *Kp, const void *V, const void *v,
+                            const int *key_len, float *C, float *P, hipStream_t st);
 // F2  masked softmax over keys, one wave per (b, i) row
 hipError_t launch_softmax(const AttnShape &s, const float *S, const int *key_len, float *P, hipStream_t st);
 // F3  context = P . V            (MFMA)
@@ -29,13 +33,16 @@ hipError_t launch_dvalue(const AttnShape &s, const float *P, const float *dC, co
                          hipStream_t st);
 // B1+B2  dP = dC . V^T (MFMA) then dS = P (dP - rowsum(P dP)); dS has row pitch ds_pitch(Tk);
 // ds_rowsum[b*Tq+i] = sum_j dS
+// order[r] = sample with the r-th most valid keys (written when order != nullptr; identity if B > kMaxSortedB)
+constexpr int kMaxSortedB = 1024;
 hipError_t launch_dscore(const AttnShape &s, const float *dC, const void *V, const float *P, const int *key_len,
-                         float *dS, float *ds_rowsum, hipStream_t st);
+                         float *dS, float *ds_rowsum, int *order, hipStream_t st);
 // B3  fused recompute: dQp, dKp, per-sample partials of dv  (dv_part [B,H]);
 // tmap != nullptr reads tanh from the stashed map instead of recomputing it
+// order (may be nullptr) maps blockIdx.y to the sample it works on
 hipError_t launch_recompute(const AttnShape &s, const void *Qp, const void *Kp, const void *v, const int *key_len,
-                            const float *dS, const float *tmap, float *dQp, float *dKp, float *dv_part,
-                            hipStream_t st);
+                            const int *order, const float *dS, const float *tmap, float *dQp, float *dKp,
+                            float *dv_part, hipStream_t st);
 // B4  dv[h] = sum_b dv_part[b,h] + sum ds_rowsum, fixed order
 hipError_t launch_dv_reduce(const AttnShape &s, const float *dv_part, const float *ds_rowsum, float *dv,
                             hipStream_t st);

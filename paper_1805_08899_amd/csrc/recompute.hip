@@ -11,7 +11,8 @@
 // dS[b,i,j] is uniform over a wave and dQp, dKp, dv are plain per-lane sums.
 // With r = 1 / (exp(2(q+k)) + 1):  t = 1 - 2r  and  1 - t^2 = 4 r (1 - r).
 // Wave w owns query rows; all waves walk the keys together in tiles of RJ.
-// Per tile a wave adds its partial column sums into LDS, and after the
+// The key tile (exponentials) and the dS tile are fetched one tile ahead and
+// shared through LDS.  Per tile a wave adds its partial column sums into LDS, and after the
 // barrier wave jj sums key jj of the tile over the waves in fixed order and
 // owns that element of dKp for the whole kernel (first block of rows stores,
 // later ones add), so no atomics are needed and results are reproducible.
@@ -81,18 +82,19 @@ __device__ __forceinline__ void rc_tile_n(int ni, const float (&fq)[RC_RI], cons
 template <typename T, bool STASH>
 __global__ __launch_bounds__(RC_THREADS) void k_recompute(
     const T *__restrict__ Qp, const T *__restrict__ Kp, const T *__restrict__ v,
-    const int *__restrict__ key_len, const float *__restrict__ dS, const float *__restrict__ tmap,
-    float *__restrict__ dQp, float *__restrict__ dKp, float *__restrict__ dv_part,
+    const int *__restrict__ key_len, const int *__restrict__ order, const float *__restrict__ dS,
+    const float *__restrict__ tmap, float *__restrict__ dQp, float *__restrict__ dKp, float *__restrict__ dv_part,
     int Tq, int Tk, int H, int pitch, int rows_per_pass) {
     // Key tile staged once per block, double buffered: exp(2k) for the factor
     // path, 2 log2e k for the exact path, and per key a flag "beyond the factor limit".
     __shared__ float s_fk[2][RC_RJ][64];
     __shared__ float s_sk[2][RC_RJ][64];
     __shared__ int s_kbig[2][RC_RJ];
+    __shared__ float s_ds[2][RC_THREADS];     // dS of the pass rows x tile keys, [row][key]
     __shared__ float s_part[2][RC_W][RC_RJ][64];
     __shared__ float s_dv[RC_W][64];
 
-    const int b = blockIdx.y;
+    const int b = order ? order[blockIdx.y] : blockIdx.y;     // samples with the most valid keys start first
     const int lane = lane_id(), w = wave_id();
     const int h = blockIdx.x * 64 + lane;
     const bool hv = h < H;
@@ -120,14 +122,24 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
     const int n_jt = (L + RC_RJ - 1) / RC_RJ;
     float accV = 0.f;
 
-    // wave w stages key w of a tile (RC_W == RC_RJ)
-    auto stage = [&](int jt, int buf) {
-        if (STASH) return;
+    // Tile staging, one tile ahead of the arithmetic.  Wave w fetches key w of the
+    // tile (RC_W == RC_RJ) and thread t the dS element (row t / 8, key t % 8) of
+    // the pass; the loads are issued before the current tile is evaluated and
+    // committed to the other LDS buffer after it.
+    const int t_row = threadIdx.x / RC_RJ, t_col = threadIdx.x % RC_RJ;
+    float kx = 0.f, dx = 0.f;
+    auto fetch = [&](int jt, int i_pass0, int nrows) {
         const int j = jt * RC_RJ + w;
-        const float x = (j < L) ? ld(kb, (size_t)j * H + hc) : 0.f;
-        s_sk[buf][w][lane] = kTwoLog2e * x;
-        s_fk[buf][w][lane] = (j < L) ? fast_exp2(kTwoLog2e * x) : 0.f;
-        const int big = __any(fabsf(x) > kFactorLimit) ? 1 : 0;
+        kx = (!STASH && j < L) ? ld(kb, (size_t)j * H + hc) : 0.f;
+        dx = (t_row < nrows) ? dsb[(size_t)(i_pass0 + t_row) * pitch + jt * RC_RJ + t_col] : 0.f;
+    };
+    auto commit = [&](int jt, int buf) {
+        const int j = jt * RC_RJ + w;
+        s_ds[buf][threadIdx.x] = dx;
+        if (STASH) return;
+        s_sk[buf][w][lane] = kTwoLog2e * kx;
+        s_fk[buf][w][lane] = (j < L) ? fast_exp2(kTwoLog2e * kx) : 0.f;
+        const int big = __any(fabsf(kx) > kFactorLimit) ? 1 : 0;
         if (lane == 0) s_kbig[buf][w] = big;
     };
 
@@ -138,25 +150,30 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
         const int ni = r_hi - r_lo;              // 0..RC_RI
         const int i0 = i_pass0 + r_lo;
 
+        fetch(0, i_pass0, nrows);
         float fq[RC_RI], sq[RC_RI], accQ[RC_RI];
         bool qbig = false;
+        {
+            float x[RC_RI];
 #pragma unroll
-        for (int a = 0; a < RC_RI; ++a) {
-            accQ[a] = 0.f;
-            float x = 0.f;
-            if (!STASH && a < ni) x = ld(qb, (size_t)(i0 + a) * H + hc);
-            qbig |= fabsf(x) > kFactorLimit;
-            sq[a] = kTwoLog2e * x;
-            fq[a] = fast_exp2(sq[a]);
+            for (int a = 0; a < RC_RI; ++a) x[a] = (!STASH && a < ni) ? ld(qb, (size_t)(i0 + a) * H + hc) : 0.f;
+#pragma unroll
+            for (int a = 0; a < RC_RI; ++a) {
+                accQ[a] = 0.f;
+                qbig |= fabsf(x[a]) > kFactorLimit;
+                sq[a] = kTwoLog2e * x[a];
+                fq[a] = fast_exp2(sq[a]);
+            }
         }
         const bool wave_qbig = __any(qbig);
-
-        stage(0, 0);
+        commit(0, 0);
         __syncthreads();
 
         for (int jt = 0; jt < n_jt; ++jt) {
             const int buf = jt & 1;
             const int j0 = jt * RC_RJ;
+            const bool more = jt + 1 < n_jt;
+            if (more) fetch(jt + 1, i_pass0, nrows);
             float accK[RC_RJ], fk[RC_RJ];
             int kcol[RC_RJ];
 #pragma unroll
@@ -164,12 +181,12 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
                 accK[c] = 0.f;
                 kcol[c] = min(j0 + c, L - 1);
             }
-            const float *ds_tile = dsb + (size_t)i0 * pitch + j0;
+            const float *ds_tile = &s_ds[buf][r_lo * RC_RJ];     // wave-uniform reads, pitch RC_RJ
             if (STASH) {
                 const float *t_tile = tmap + (((size_t)b * Tq + i0) * Tk) * H + hc;
 #pragma unroll
                 for (int c = 0; c < RC_RJ; ++c) fk[c] = 0.f;
-                rc_tile_n<RC_STASH>(ni, fq, fk, ds_tile, pitch, t_tile, (size_t)Tk * H, (size_t)H, kcol, accQ, accK,
+                rc_tile_n<RC_STASH>(ni, fq, fk, ds_tile, RC_RJ, t_tile, (size_t)Tk * H, (size_t)H, kcol, accQ, accK,
                                     accV);
             } else {
                 int kbig = 0;
@@ -178,14 +195,14 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
                 if (!(wave_qbig || kbig)) {
 #pragma unroll
                     for (int c = 0; c < RC_RJ; ++c) fk[c] = s_fk[buf][c][lane];
-                    rc_tile_n<RC_FACTOR>(ni, fq, fk, ds_tile, pitch, nullptr, 0, 0, kcol, accQ, accK, accV);
+                    rc_tile_n<RC_FACTOR>(ni, fq, fk, ds_tile, RC_RJ, nullptr, 0, 0, kcol, accQ, accK, accV);
                 } else {
 #pragma unroll
                     for (int c = 0; c < RC_RJ; ++c) fk[c] = s_sk[buf][c][lane];
-                    rc_tile_n<RC_EXACT>(ni, sq, fk, ds_tile, pitch, nullptr, 0, 0, kcol, accQ, accK, accV);
+                    rc_tile_n<RC_EXACT>(ni, sq, fk, ds_tile, RC_RJ, nullptr, 0, 0, kcol, accQ, accK, accV);
                 }
             }
-            if (jt + 1 < n_jt) stage(jt + 1, buf ^ 1);
+            if (more) commit(jt + 1, buf ^ 1);
 #pragma unroll
             for (int c = 0; c < RC_RJ; ++c) s_part[buf][w][c][lane] = accK[c];
             __syncthreads();
@@ -221,28 +238,28 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
 
 template <typename T>
 static hipError_t launch_recompute_t(const AttnShape &s, const void *Qp, const void *Kp, const void *v,
-                                     const int *key_len, const float *dS, const float *tmap, float *dQp,
-                                     float *dKp, float *dv_part, hipStream_t st) {
+                                     const int *key_len, const int *order, const float *dS, const float *tmap,
+                                     float *dQp, float *dKp, float *dv_part, hipStream_t st) {
     const int max_rows = RC_W * RC_RI;
     const int n_pass = (s.Tq + max_rows - 1) / max_rows;
     const int rows_per_pass = (s.Tq + n_pass - 1) / n_pass;
     dim3 grid((s.H + 63) / 64, s.B);
     if (tmap)
-        k_recompute<T, true><<<grid, RC_THREADS, 0, st>>>((const T *)Qp, (const T *)Kp, (const T *)v, key_len, dS,
-                                                          tmap, dQp, dKp, dv_part, s.Tq, s.Tk, s.H,
+        k_recompute<T, true><<<grid, RC_THREADS, 0, st>>>((const T *)Qp, (const T *)Kp, (const T *)v, key_len, order,
+                                                          dS, tmap, dQp, dKp, dv_part, s.Tq, s.Tk, s.H,
                                                           ds_pitch(s.Tk), rows_per_pass);
     else
-        k_recompute<T, false><<<grid, RC_THREADS, 0, st>>>((const T *)Qp, (const T *)Kp, (const T *)v, key_len, dS,
-                                                           tmap, dQp, dKp, dv_part, s.Tq, s.Tk, s.H,
+        k_recompute<T, false><<<grid, RC_THREADS, 0, st>>>((const T *)Qp, (const T *)Kp, (const T *)v, key_len, order,
+                                                           dS, tmap, dQp, dKp, dv_part, s.Tq, s.Tk, s.H,
                                                            ds_pitch(s.Tk), rows_per_pass);
     return hipGetLastError();
 }
 
 hipError_t launch_recompute(const AttnShape &s, const void *Qp, const void *Kp, const void *v, const int *key_len,
-                            const float *dS, const float *tmap, float *dQp, float *dKp, float *dv_part,
-                            hipStream_t st) {
-    return s.bf16 ? launch_recompute_t<bf16_t>(s, Qp, Kp, v, key_len, dS, tmap, dQp, dKp, dv_part, st)
-                  : launch_recompute_t<float>(s, Qp, Kp, v, key_len, dS, tmap, dQp, dKp, dv_part, st);
+                            const int *order, const float *dS, const float *tmap, float *dQp, float *dKp,
+                            float *dv_part, hipStream_t st) {
+    return s.bf16 ? launch_recompute_t<bf16_t>(s, Qp, Kp, v, key_len, order, dS, tmap, dQp, dKp, dv_part, st)
+                  : launch_recompute_t<float>(s, Qp, Kp, v, key_len, order, dS, tmap, dQp, dKp, dv_part, st);
 }
 
 }  // namespace echo

@@ -34,26 +34,38 @@ hipError_t launch_softmax(const AttnShape &s, const float *S, const int *key_len
     return hipGetLastError();
 }
 
-// dv[h] = c0 + sum_b dv_part[b,h], b ascending; c0 = sum over all rows of
-// ds_rowsum (the part of sum dS*tanh that comes from tanh = 1 - 2r; it is zero
-// in exact arithmetic because every row of dS sums to zero).
-__global__ __launch_bounds__(64) void k_dv_reduce(const float *__restrict__ dv_part,
+// dv[h] = c0 + sum_b dv_part[b,h];  c0 = sum over all rows of ds_rowsum (the
+// part of sum dS*tanh that comes from tanh = 1 - 2r; it is zero in exact
+// arithmetic because every row of dS sums to zero).  Block = 64 values of h x
+// 4 groups of samples; every partial sum and the final combination run in a
+// fixed order, so the result is reproducible.
+__global__ __launch_bounds__(256) void k_dv_reduce(const float *__restrict__ dv_part,
                                                   const float *__restrict__ ds_rowsum, float *__restrict__ dv,
                                                   int B, int rows, int H) {
-    const int lane = lane_id();
+    __shared__ float s_c0[256];
+    __shared__ float s_acc[4][64];
+    const int lane = lane_id(), g = wave_id();
     float c0 = 0.f;
-    for (int r = lane; r < rows; r += 64) c0 += ds_rowsum[r];
-    c0 = wave_sum(c0);
+    for (int r = threadIdx.x; r < rows; r += 256) c0 += ds_rowsum[r];
+    s_c0[threadIdx.x] = c0;
     const int h = blockIdx.x * 64 + lane;
-    if (h >= H) return;
     float acc = 0.f;
-    for (int b = 0; b < B; ++b) acc += dv_part[(size_t)b * H + h];
-    dv[h] = acc + c0;
+    if (h < H)
+        for (int b = g; b < B; b += 4) acc += dv_part[(size_t)b * H + h];
+    s_acc[g][lane] = acc;
+    __syncthreads();
+    if (g == 0) {
+        float c = 0.f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) c += s_c0[lane + 64 * k];
+        c = wave_sum(c);
+        if (h < H) dv[h] = ((s_acc[0][lane] + s_acc[1][lane]) + (s_acc[2][lane] + s_acc[3][lane])) + c;
+    }
 }
 
 hipError_t launch_dv_reduce(const AttnShape &s, const float *dv_part, const float *ds_rowsum, float *dv,
                             hipStream_t st) {
-    k_dv_reduce<<<(s.H + 63) / 64, 64, 0, st>>>(dv_part, ds_rowsum, dv, s.B, s.B * s.Tq, s.H);
+    k_dv_reduce<<<(s.H + 63) / 64, 256, 0, st>>>(dv_part, ds_rowsum, dv, s.B, s.B * s.Tq, s.H);
     return hipGetLastError();
 }
 
