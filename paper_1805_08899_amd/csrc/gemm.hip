@@ -50,16 +50,29 @@ __global__ __launch_bounds__(256) void k_pv(const float *__restrict__ P, const T
 
     if (m0 < Mvalid) {
         const int m = m0 + lm;
-        for (int k0 = 0; k0 < K; k0 += 4) {
-            const int k = k0 + lk;
-            float a = 0.f;
-            if (m < Mvalid && k < K) a = TRANS_A ? Pb[(size_t)k * Tk + m] : Pb[(size_t)m * Tk + k];
-            float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (k < K && nok) bv = ld4(Bb, (size_t)k * N + ncol);
-            acc[0] = mfma16(a, bv.x, acc[0]);
-            acc[1] = mfma16(a, bv.y, acc[1]);
-            acc[2] = mfma16(a, bv.z, acc[2]);
-            acc[3] = mfma16(a, bv.w, acc[3]);
+        constexpr int U = 8;                      // k-steps whose loads are in flight together
+        for (int kb0 = 0; kb0 < K; kb0 += 4 * U) {
+            float a[U];
+            float4 bv[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int k = kb0 + 4 * u + lk;
+                a[u] = 0.f;
+                bv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (kb0 + 4 * u < K) {            // uniform
+                    if (m < Mvalid && k < K) a[u] = TRANS_A ? Pb[(size_t)k * Tk + m] : Pb[(size_t)m * Tk + k];
+                    if (k < K && nok) bv[u] = ld4(Bb, (size_t)k * N + ncol);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (kb0 + 4 * u < K) {
+                    acc[0] = mfma16(a[u], bv[u].x, acc[0]);
+                    acc[1] = mfma16(a[u], bv[u].y, acc[1]);
+                    acc[2] = mfma16(a[u], bv[u].z, acc[2]);
+                    acc[3] = mfma16(a[u], bv[u].w, acc[3]);
+                }
+            }
         }
     }
     if (!nok) return;
@@ -103,7 +116,7 @@ template <typename TV>
 __global__ __launch_bounds__(256) void k_dscore(const float *__restrict__ dC, const TV *__restrict__ V,
                                                 const float *__restrict__ P, const int *__restrict__ key_len,
                                                 float *__restrict__ dS, float *__restrict__ ds_rowsum,
-                                                int *__restrict__ order, int B, int sorted,
+                                                int *__restrict__ order, int B, int sorted, int fold,
                                                 int Tq, int Tk, int Dv, int pitch) {
     extern __shared__ float s_dp[];           // [16][pitch16]
     const int b = blockIdx.y;
@@ -119,7 +132,10 @@ __global__ __launch_bounds__(256) void k_dscore(const float *__restrict__ dC, co
                     r += (lo > lc) || (lo == lc && o < cand);
                 }
             }
-            order[r] = cand;
+            // fold: when the whole grid is resident at once, blocks y and y + B/2 meet on one CU
+            // (two blocks per CU, placed in launch order), so the second half runs lightest first
+            const int half = (B + 1) / 2;
+            order[(fold && r >= half) ? half + (B - 1 - r) : r] = cand;
         }
     }
     const int i0 = blockIdx.x * 16;
@@ -135,17 +151,28 @@ __global__ __launch_bounds__(256) void k_dscore(const float *__restrict__ dC, co
         const int i = i0 + lm, j = jt * 16 + lm;
         const bool iok = i < Tq, jok = j < L;
         f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
-        for (int d0 = 0; d0 < Dv; d0 += 16) {
-            const int d = d0 + 4 * lk;
-            float4 a = make_float4(0.f, 0.f, 0.f, 0.f), bv = a;
-            if (d < Dv) {
-                if (iok) a = ld4(dCb, (size_t)i * Dv + d);
-                if (jok) bv = ld4(Vb, (size_t)j * Dv + d);
+        constexpr int U = 8;                      // 16-wide slices of d whose loads are in flight together
+        for (int db0 = 0; db0 < Dv; db0 += 16 * U) {
+            float4 a[U], bv[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int d = db0 + 16 * u + 4 * lk;
+                a[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                bv[u] = a[u];
+                if (d < Dv) {
+                    if (iok) a[u] = ld4(dCb, (size_t)i * Dv + d);
+                    if (jok) bv[u] = ld4(Vb, (size_t)j * Dv + d);
+                }
             }
-            acc = mfma16(a.x, bv.x, acc);
-            acc = mfma16(a.y, bv.y, acc);
-            acc = mfma16(a.z, bv.z, acc);
-            acc = mfma16(a.w, bv.w, acc);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (db0 + 16 * u < Dv) {
+                    acc = mfma16(a[u].x, bv[u].x, acc);
+                    acc = mfma16(a[u].y, bv[u].y, acc);
+                    acc = mfma16(a[u].z, bv[u].z, acc);
+                    acc = mfma16(a[u].w, bv[u].w, acc);
+                }
+            }
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) s_dp[(4 * lk + r) * pitch16 + jt * 16 + lm] = acc[r];
@@ -176,6 +203,7 @@ __global__ __launch_bounds__(256) void k_dscore(const float *__restrict__ dC, co
 hipError_t launch_dscore(const AttnShape &s, const float *dC, const void *V, const float *P, const int *key_len,
                          float *dS, float *ds_rowsum, int *order, hipStream_t st) {
     const int sorted = s.B <= kMaxSortedB ? 1 : 0;
+    const int fold = (sorted && (long long)s.B * ((s.H + 63) / 64) <= 512) ? 1 : 0;   // recompute grid in one round
     dim3 grid((s.Tq + 15) / 16, s.B);
     const int pitch16 = (s.Tk + 15) / 16 * 16 + 4;
     const size_t lds = (size_t)16 * pitch16 * sizeof(float);
@@ -187,10 +215,10 @@ hipError_t launch_dscore(const AttnShape &s, const float *dC, const void *V, con
         if (e != hipSuccess) return e;
     }
     if (s.bf16)
-        k_dscore<bf16_t><<<grid, 256, lds, st>>>(dC, (const bf16_t *)V, P, key_len, dS, ds_rowsum, order, s.B, sorted,
+        k_dscore<bf16_t><<<grid, 256, lds, st>>>(dC, (const bf16_t *)V, P, key_len, dS, ds_rowsum, order, s.B, sorted, fold,
                                                  s.Tq, s.Tk, s.Dv, ds_pitch(s.Tk));
     else
-        k_dscore<float><<<grid, 256, lds, st>>>(dC, (const float *)V, P, key_len, dS, ds_rowsum, order, s.B, sorted,
+        k_dscore<float><<<grid, 256, lds, st>>>(dC, (const float *)V, P, key_len, dS, ds_rowsum, order, s.B, sorted, fold,
                                                 s.Tq, s.Tk, s.Dv, ds_pitch(s.Tk));
     return hipGetLastError();
 }

@@ -45,13 +45,27 @@ __global__ __launch_bounds__(256) void k_dv_reduce(const float *__restrict__ dv_
     __shared__ float s_c0[256];
     __shared__ float s_acc[4][64];
     const int lane = lane_id(), g = wave_id();
+    // loads go out eight at a time so that their latencies overlap
     float c0 = 0.f;
-    for (int r = threadIdx.x; r < rows; r += 256) c0 += ds_rowsum[r];
+    for (int r0 = threadIdx.x; r0 < rows; r0 += 8 * 256) {
+        float x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x[u] = (r0 + u * 256 < rows) ? ds_rowsum[r0 + u * 256] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) c0 += x[u];
+    }
     s_c0[threadIdx.x] = c0;
     const int h = blockIdx.x * 64 + lane;
     float acc = 0.f;
-    if (h < H)
-        for (int b = g; b < B; b += 4) acc += dv_part[(size_t)b * H + h];
+    if (h < H) {
+        for (int b0 = g; b0 < B; b0 += 8 * 4) {
+            float x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) x[u] = (b0 + 4 * u < B) ? dv_part[(size_t)(b0 + 4 * u) * H + h] : 0.f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += x[u];
+        }
+    }
     s_acc[g][lane] = acc;
     __syncthreads();
     if (g == 0) {
