@@ -4,27 +4,33 @@
 // one fused kernel instead of many small ones, fewer launches and accesses).
 //
 // Block = (sample b, FW_R query rows), 8 waves, two blocks per CU.
-//   A  exp(2q) and 2 log2e q of the rows go to LDS (taken once per block).
+//   A  exp(2q) of the rows goes to LDS (taken once per block).
 //   B  keys are dealt to the waves round-robin, FW_RJ per wave and chunk of 32;
 //      lanes run along h.  A wave loads its own key rows straight from memory
 //      (every K element is exponentiated once per block), evaluates its rows x
 //      keys register tile slice by slice of 64 h
 //          acc += v[h] * rcp(fma(exp(2q), exp(2k), 1))
-//      and finishes with one transposing wave reduction per tile.
+//      and finishes with one transposing wave reduction per tile.  A tile that
+//      met a pre-activation beyond the factorisation limit is redone by a
+//      small exact routine that exponentiates the sum.
 //   C  wave r normalises row r (softmax over the valid keys), writes P.
 //   D  context = P V on the matrix cores: v_mfma_f32_4x4x1 treats the 64 lanes
 //      as 16 column groups of 4, so a lane owns one output column and reads V
 //      rows with plain coalesced loads.
 //
 // The whole pass of a block is short compared with a trip to memory, so every
-// phase issues its loads in deep batches before it consumes them, and nothing
-// that is loaded first depends on key_len: query rows and the first key slices
-// leave before anything is waited for, key slices run FW_PF ahead of the
+// phase issues its loads in batches before it consumes them: query rows and
+// the first key slices leave together, key slices run FW_PF ahead of the
 // arithmetic, and the first FW_KB value rows leave before the softmax.
 //
-// Two 8-wave blocks share a CU, so a CU works through the sum of its two
-// tiles at full rate whatever their mix of key lengths.  The tiles of one
-// sample share an XCD (and its L2).
+// Placement.  Two 8-wave blocks share a CU; the hardware hands blocks to the
+// XCDs round-robin and, while every block of the grid fits at once, block i
+// and block i + 256 land on the same CU.  The kernel ranks the samples by
+// valid keys, deals them to the XCDs in snake order (equal work per XCD, and
+// all tiles of a sample share one L2), and inside an XCD gives the CUs that
+// hold one block the heaviest tiles and pairs heavy with light tiles on the
+// others.  With more than two rounds of blocks it simply starts the heaviest
+// first.  The mapping only moves work around; results do not depend on it.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -48,16 +54,19 @@ constexpr int FW_W = 8;          // waves per block
 constexpr int FW_CHUNK = FW_W * FW_RJ;   // keys per chunk
 constexpr int FW_THREADS = 64 * FW_W;
 constexpr int FW_XCD = 8;        // blockIdx.x mod 8 selects the XCD
+constexpr int FW_CU_PER_XCD = 32;
 constexpr int FW_PF = 4;         // slices of h whose key values are in flight per wave
 constexpr int FW_KB = 32;        // value rows in flight per wave in the context phase
+constexpr int FW_MAX_RANKED_B = 1024;   // the in-kernel ranking is quadratic in B
 
-// One wave, NJ keys (rows krow0 + c*kstride), all slices of h.  s_e / s_s: LDS rows of exp(2q) /
-// 2 log2e q, pitch Hp.  FULL: all FW_R rows are live, else the first ni.  kx[u][c] / vx[u] arrive
-// holding slices 0..FW_PF-1 of the wave's keys and of v (invalid lanes of v hold 0) and are
-// refilled FW_PF slices ahead.
+// One wave, NJ keys (rows krow0 + c*kstride), all slices of h, factor path only.  s_e: LDS rows of
+// exp(2q), pitch Hp (rows past ni hold zeros).  FULL: all FW_R rows are live, else the first ni.
+// kx[u][c] / vx[u] arrive holding slices 0..FW_PF-1 of the wave's keys and of v (invalid lanes of v
+// hold 0); the ring is rotated every slice and refilled FW_PF slices ahead.  Returns true if a key value was beyond the factor
+// limit, in which case nothing was written and the caller must redo the tile exactly.
 template <typename T, int NJ, bool FULL>
-__device__ __forceinline__ void fw_score_wave(const float *__restrict__ s_e, const float *__restrict__ s_s, int Hp,
-                                              int ni, bool qbig, const T *__restrict__ krow0, size_t kstride, int H,
+__device__ __forceinline__ bool fw_score_wave(const float *__restrict__ s_e, int Hp, int ni,
+                                              const T *__restrict__ krow0, size_t kstride, int H,
                                               const T *__restrict__ v, float *__restrict__ s_S, int spitch,
                                               int jcol0, float (&kx)[FW_PF][FW_RJ], float (&vx)[FW_PF]) {
     const int lane = lane_id();
@@ -67,73 +76,47 @@ __device__ __forceinline__ void fw_score_wave(const float *__restrict__ s_e, con
 #pragma unroll
         for (int c = 0; c < NJ; ++c) acc[a][c] = 0.f;
     float vsum = 0.f;
+    bool kbig = false;
     const int nsl = (H + 63) / 64;
 
-    for (int s0 = 0; s0 < nsl; s0 += FW_PF) {
-#ifdef ECHO_TIMING
-        if (s0 == FW_PF && jcol0 < FW_W) FW_STAMP(1);
-#endif
+    for (int sl = 0; sl < nsl; ++sl) {
+        const int h0 = sl * 64;
+        const float vh = vx[0];
+        const bool hv = h0 + lane < H;
+        float fk[NJ];
 #pragma unroll
-        for (int u = 0; u < FW_PF; ++u) {
-            const int sl = s0 + u;
-            if (sl < nsl) {
-                const int h0 = sl * 64;
-                const float vh = vx[u];
-                const bool hv = h0 + lane < H;
-                bool kbig = false;
-                float fk[NJ];                 // 2 log2e k of this slice; turned into exp(2k) on the factor path
+        for (int c = 0; c < NJ; ++c) {
+            const float x = hv ? kx[0][c] : 0.f;
+            kbig |= fabsf(x) > kFactorLimit;
+            fk[c] = fast_exp2(kTwoLog2e * x);
+        }
+        // rotate the ring (the loop stays rolled, so the code stays small) and refill its last slot
 #pragma unroll
-                for (int c = 0; c < NJ; ++c) {
-                    const float x = hv ? kx[u][c] : 0.f;
-                    kbig |= fabsf(x) > kFactorLimit;
-                    fk[c] = kTwoLog2e * x;
-                }
-#ifdef ECHO_TIMING
-                if (sl == 0 && jcol0 < FW_W) {
-                    asm volatile("" ::"v"(fk[0]), "v"(vh));
-                    FW_STAMP(2);
-                }
-#endif
-                if (sl + FW_PF < nsl) {       // refill this ring slot
-                    const int hn = h0 + FW_PF * 64 + lane;
-                    const int hc = hn < H ? hn : H - 1;
+        for (int u = 0; u + 1 < FW_PF; ++u) {
 #pragma unroll
-                    for (int c = 0; c < NJ; ++c) kx[u][c] = ld(krow0, (size_t)c * kstride + hc);
-                    vx[u] = hn < H ? ld(v, hc) : 0.f;
-                }
-                vsum += vh;
-                const bool exact = qbig || __any(kbig);
-                const float *qrow = (exact ? s_s : s_e) + h0 + lane;
-                float fq[FW_R];               // rows past ni hold zeros in LDS
+            for (int c = 0; c < NJ; ++c) kx[u][c] = kx[u + 1][c];
+            vx[u] = vx[u + 1];
+        }
+        if (sl + FW_PF < nsl) {
+            const int hn = h0 + FW_PF * 64 + lane;
+            const int hc = hn < H ? hn : H - 1;
 #pragma unroll
-                for (int a = 0; a < FW_R; ++a) fq[a] = qrow[a * Hp];
-                if (!exact) {
+            for (int c = 0; c < NJ; ++c) kx[FW_PF - 1][c] = ld(krow0, (size_t)c * kstride + hc);
+            vx[FW_PF - 1] = hn < H ? ld(v, hc) : 0.f;
+        }
+        vsum += vh;
+        float fq[FW_R];
 #pragma unroll
-                    for (int c = 0; c < NJ; ++c) fk[c] = fast_exp2(fk[c]);
+        for (int a = 0; a < FW_R; ++a) fq[a] = s_e[a * Hp + h0 + lane];
 #pragma unroll
-                    for (int a = 0; a < FW_R; ++a) {
-                        if (FULL || a < ni) {
+        for (int a = 0; a < FW_R; ++a) {
+            if (FULL || a < ni) {
 #pragma unroll
-                            for (int c = 0; c < NJ; ++c)
-                                acc[a][c] = __builtin_fmaf(vh, r_from_factors(fq[a], fk[c]), acc[a][c]);
-                        }
-                    }
-                } else {
-#pragma unroll
-                    for (int a = 0; a < FW_R; ++a) {
-                        if (FULL || a < ni) {
-#pragma unroll
-                            for (int c = 0; c < NJ; ++c)
-                                acc[a][c] = __builtin_fmaf(vh, r_from_sum(fq[a], fk[c]), acc[a][c]);
-                        }
-                    }
-                }
+                for (int c = 0; c < NJ; ++c) acc[a][c] = __builtin_fmaf(vh, r_from_factors(fq[a], fk[c]), acc[a][c]);
             }
         }
     }
-#ifdef ECHO_TIMING
-    if (jcol0 < FW_W) FW_STAMP(5);
-#endif
+    if (__any(kbig)) return true;
     // S = sum_h v (1 - 2r): per lane first, then one transposing reduction for the whole tile
     constexpr int NP = FW_R * NJ;
     constexpr int NPOW = NP <= 8 ? 8 : NP <= 16 ? 16 : NP <= 32 ? 32 : 64;
@@ -147,31 +130,100 @@ __device__ __forceinline__ void fw_score_wave(const float *__restrict__ s_e, con
     const int p = lane / (64 / NPOW);
     if ((lane % (64 / NPOW)) == 0 && p < NP) {
         const int a = p / NJ, c = p % NJ;
-        if (a < ni && jcol0 + c * FW_W < spitch - 4) s_S[a * spitch + jcol0 + c * FW_W] = tot;
+        if (a < ni) s_S[a * spitch + jcol0 + c * FW_W] = tot;
     }
+    return false;
+}
+
+// The same tile with tanh taken from the exponential of the sum: correct for any finite input.
+// Straightforward loops; only reached for pre-activations beyond the factor limit.
+template <typename T>
+__device__ __noinline__ void fw_score_wave_exact(const T *__restrict__ qrow0, int ni, const T *__restrict__ krow0,
+                                                 size_t kstride, int nj, int H, const T *__restrict__ v,
+                                                 float *__restrict__ s_S, int spitch, int jcol0) {
+    const int lane = lane_id();
+    for (int a = 0; a < ni; ++a) {
+        for (int c = 0; c < nj; ++c) {
+            float acc = 0.f;
+            for (int h = lane; h < H; h += 64) {
+                const float sq = kTwoLog2e * ld(qrow0, (size_t)a * H + h);
+                const float sk = kTwoLog2e * ld(krow0, (size_t)c * kstride + h);
+                const float vh = ld(v, h);
+                acc += vh * __builtin_fmaf(-2.f, r_from_sum(sq, sk), 1.f);
+            }
+            acc = wave_sum(acc);
+            if (lane == 0) s_S[a * spitch + jcol0 + c * FW_W] = acc;
+        }
+    }
+}
+
+// Which (sample, row tile) this block works on; see "Placement" at the top.  s_i: scratch of
+// 2*B + 2 ints in LDS.  Returns false if the block has nothing to do.
+__device__ __forceinline__ bool fw_pick_item(const int *__restrict__ key_len, int B, int Tq, int Tk, int tiles,
+                                             int ranked, int *s_i, int &b, int &tile) {
+    const int xcd = blockIdx.x % FW_XCD, li = blockIdx.x / FW_XCD;
+    if (!ranked) {                         // samples x, x+8, ... on XCD x, in index order
+        b = xcd + FW_XCD * (li / tiles);
+        tile = li % tiles;
+        return b < B;
+    }
+    int *s_len = s_i, *s_xb = s_i + B, *s_cnt = s_i + 2 * B;
+    for (int o = threadIdx.x; o < B; o += FW_THREADS) s_len[o] = clamp_len(key_len[o], Tk);
+    if (threadIdx.x == 0) *s_cnt = 0;
+    __syncthreads();
+    for (int cand = threadIdx.x; cand < B; cand += FW_THREADS) {
+        const int lc = s_len[cand];
+        int r = 0;                         // rank by valid keys, most first, ties by index
+        for (int o = 0; o < B; ++o) {
+            const int lo = s_len[o];
+            r += (lo > lc) || (lo == lc && o < cand);
+        }
+        const int q = r % (2 * FW_XCD);
+        const int x = q < FW_XCD ? q : 2 * FW_XCD - 1 - q;     // snake over the XCDs
+        if (x == xcd) {
+            s_xb[(r / (2 * FW_XCD)) * 2 + (q >= FW_XCD ? 1 : 0)] = cand;   // position inside the XCD, heaviest first
+            atomicAdd(s_cnt, 1);
+        }
+    }
+    __syncthreads();
+    const int M = *s_cnt;                  // samples of this XCD
+    const int n = M * tiles;               // its tiles
+    if (li >= n) return false;
+    // position in the launch order -> position in "heaviest first" order
+    int rho = li;
+    if (n > FW_CU_PER_XCD && n <= 2 * FW_CU_PER_XCD) {
+        const int singles = 2 * FW_CU_PER_XCD - n;             // CUs that get one block: the heaviest tiles
+        if (li >= FW_CU_PER_XCD) rho = n - 1 - (li - FW_CU_PER_XCD);
+        else if (li >= FW_CU_PER_XCD - singles) rho = li - (FW_CU_PER_XCD - singles);
+        else rho = singles + li;
+    }
+    // heaviest-first list: sample by sample (the tiles of a sample weigh the same)
+    const int m = rho / tiles;
+    tile = rho % tiles;
+    b = s_xb[m];
+    return true;
 }
 
 template <typename T>
 __global__ __launch_bounds__(FW_THREADS, 4) void k_fwd_fused(
     const T *__restrict__ Qp, const T *__restrict__ Kp, const T *__restrict__ V, const T *__restrict__ v,
     const int *__restrict__ key_len, float *__restrict__ C, float *__restrict__ P,
-    int B, int Tq, int Tk, int H, int Dv, int tiles, int Hp, int spitch) {
+    int B, int Tq, int Tk, int H, int Dv, int tiles, int Hp, int spitch, int ranked) {
     extern __shared__ float smem[];
     float *s_e = smem;                       // [FW_R][Hp]  exp(2q)
-    float *s_s = s_e + FW_R * Hp;            // [FW_R][Hp]  2 log2e q
-    float *s_S = s_s + FW_R * Hp;            // [FW_R][spitch]  scores, then probabilities
+    float *s_S = s_e + FW_R * Hp;            // [FW_R][spitch]  scores, then probabilities
 
     const int lane = lane_id(), w = wave_id();
     FW_STAMP(0);
 
-    // ---- which (sample, row tile): XCD x takes samples x, x+8, ...
-    const int xcd = blockIdx.x % FW_XCD, idx = blockIdx.x / FW_XCD;
-    const int b = xcd + FW_XCD * (idx / tiles), tile = idx % tiles;
-    if (b >= B) return;
-    const int r0 = tile * FW_R;
-    const int ni = min(FW_R, Tq - r0);                        // 1..FW_R
+    int b, tile;
+    if (!fw_pick_item(key_len, B, Tq, Tk, tiles, ranked, reinterpret_cast<int *>(smem), b, tile)) return;
+    if (ranked) __syncthreads();             // the scratch is about to be overwritten by the staging
+    const int r0 = (int)(((long long)Tq * tile) / tiles);      // rows are split evenly over the tiles
+    const int ni = (int)(((long long)Tq * (tile + 1)) / tiles) - r0;   // 1..FW_R
+    FW_STAMP(1);
 
-    // ---- loads that do not depend on key_len go out first: the query rows ...
+    // ---- loads first: the query rows ...
     const T *qb = Qp + ((size_t)b * Tq + r0) * H;
     constexpr int QMAX = 2;                                   // column passes per batch (H <= 1024 in one batch)
     float qx[QMAX][FW_R];
@@ -214,8 +266,11 @@ __global__ __launch_bounds__(FW_THREADS, 4) void k_fwd_fused(
         for (int e = threadIdx.x; e < ni * Dv; e += FW_THREADS) Cb[e] = 0.f;
         return;
     }
+#ifdef ECHO_TIMING
+    if (threadIdx.x == 0 && blockIdx.x < 16384) g_stamps[blockIdx.x * 8 + 2] = ((long long)b << 40) | ((long long)tile << 24) | ((long long)ni << 16) | L;
+#endif
 
-    // ---- A: exp(2q) and 2 log2e q to LDS (rows past ni and columns past H as zeros)
+    // ---- A: exp(2q) to LDS (rows past ni and columns past H as zeros)
     bool big = false;
     for (int col0 = 0; col0 < Hp; col0 += QMAX * FW_THREADS) {
         if (col0 > 0) q_fetch(col0);
@@ -226,9 +281,7 @@ __global__ __launch_bounds__(FW_THREADS, 4) void k_fwd_fused(
 #pragma unroll
                 for (int a = 0; a < FW_R; ++a) {
                     big |= fabsf(qx[m][a]) > kFactorLimit;
-                    const float sc = kTwoLog2e * qx[m][a];
-                    s_s[a * Hp + h] = sc;
-                    s_e[a * Hp + h] = (a < ni && h < H) ? fast_exp2(sc) : 0.f;
+                    s_e[a * Hp + h] = (a < ni && h < H) ? fast_exp2(kTwoLog2e * qx[m][a]) : 0.f;
                 }
             }
         }
@@ -244,22 +297,20 @@ __global__ __launch_bounds__(FW_THREADS, 4) void k_fwd_fused(
         const int nj = j0 < L ? min(FW_RJ, (L - 1 - j0) / FW_W + 1) : 0;
         const T *krow0 = kb + (size_t)j0 * H;
         const size_t kstride = (size_t)FW_W * H;
-#define FW_CASE(N)                                                                                              \
-    case N:                                                                                                     \
-        if (ni == FW_R)                                                                                         \
-            fw_score_wave<T, N, true>(s_e, s_s, Hp, ni, qbig, krow0, kstride, H, v, s_S, spitch, j0, kx, vx);   \
-        else                                                                                                    \
-            fw_score_wave<T, N, false>(s_e, s_s, Hp, ni, qbig, krow0, kstride, H, v, s_S, spitch, j0, kx, vx);  \
+        bool redo = qbig && nj > 0;
+        if (!qbig) {
+#define FW_CASE(N)                                                                                         \
+    case N:                                                                                                \
+        redo = (ni == FW_R) ? fw_score_wave<T, N, true>(s_e, Hp, ni, krow0, kstride, H, v, s_S, spitch, j0, kx, vx) \
+                            : fw_score_wave<T, N, false>(s_e, Hp, ni, krow0, kstride, H, v, s_S, spitch, j0, kx, vx); \
         break;
-#ifdef FW_ONE_VARIANT
-        if (nj > 0) fw_score_wave<T, 4, false>(s_e, s_s, Hp, ni, qbig, krow0, kstride, H, v, s_S, spitch, j0, kx, vx);
-#else
-        switch (nj) {
-            FW_CASE(1) FW_CASE(2) FW_CASE(3) FW_CASE(4)
-            default: break;
-        }
-#endif
+            switch (nj) {
+                FW_CASE(1) FW_CASE(2) FW_CASE(3) FW_CASE(4)
+                default: break;
+            }
 #undef FW_CASE
+        }
+        if (redo) fw_score_wave_exact<T>(qb, ni, krow0, kstride, nj, H, v, s_S, spitch, j0);
     }
 
     // first batch of value rows for the context phase leaves before the softmax
@@ -303,6 +354,7 @@ __global__ __launch_bounds__(FW_THREADS, 4) void k_fwd_fused(
         }
     }
     __syncthreads();
+    FW_STAMP(5);
 
     // ---- D: context rows = P V.  A wave takes 64 columns at a time; lane l owns column n0 + l.
     // One 4x4x1 MFMA multiplies 4 rows of P (replicated over the 16 lane groups) with one V value per lane.
@@ -354,7 +406,9 @@ extern "C" int echo_debug_stamps(long long *host, int n) {
 size_t fwd_fused_lds_bytes(const AttnShape &s) {
     const int Hp = (s.H + 63) / 64 * 64;
     const int spitch = ((s.Tk + 3) & ~3) + 4;
-    return (size_t)(2 * FW_R * Hp + FW_R * spitch) * sizeof(float);
+    const size_t stage = (size_t)(FW_R * Hp + FW_R * spitch) * sizeof(float);
+    const size_t rank_scratch = (size_t)(2 * s.B + 2) * sizeof(int);
+    return stage > rank_scratch ? stage : rank_scratch;
 }
 
 template <typename T>
@@ -373,8 +427,9 @@ static hipError_t launch_fwd_fused_t(const AttnShape &s, const void *Qp, const v
     const int tiles = (s.Tq + FW_R - 1) / FW_R;
     const int samples_per_xcd = (s.B + FW_XCD - 1) / FW_XCD;
     const int grid = FW_XCD * samples_per_xcd * tiles;
+    const int ranked = s.B <= FW_MAX_RANKED_B ? 1 : 0;
     k_fwd_fused<T><<<grid, FW_THREADS, lds, st>>>((const T *)Qp, (const T *)Kp, (const T *)V, (const T *)v, key_len, C,
-                                                  P, s.B, s.Tq, s.Tk, s.H, s.Dv, tiles, Hp, spitch);
+                                                  P, s.B, s.Tq, s.Tk, s.H, s.Dv, tiles, Hp, spitch, ranked);
     return hipGetLastError();
 }
 
