@@ -22,17 +22,22 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# MI355X: 256 CUs x 4 SIMDs x 16 fp32 lanes at 2.4 GHz -> vector instruction
-# issue slots per second (one slot = one fp32 lane-operation, FMA counts once).
-PEAK_LANEOPS = 256 * 4 * 16 * 2.4e9          # 39.3e12
+# MI355X vector ALUs: 256 CUs x 4 SIMDs, one 64-lane fp32 instruction per SIMD every 2 clocks at 2.4 GHz
+# = 78.6e12 lane-operation issue slots per second; counting every slot as an FMA (2 flop) this is the
+# published 157.3 TFLOP/s fp32 vector peak.  v_rcp_f32 / v_exp_f32 hold the pipe for 8 clocks = 4 slots.
+PEAK_SLOTS = 256 * 4 * 32 * 2.4e9            # 78.6e12 slots/s
+PEAK_TFLOPS = 2 * PEAK_SLOTS / 1e12          # 157.3
 PEAK_HBM = 8.0e12
-# Issue-slot cost per tanh evaluation of the two hot loops as written
-# (transcendentals issue at a quarter of the fp32 rate):
-#   score loop     fma, rcp, fma            -> 2 + 4 = 6 slots
-#   recompute loop fma, rcp, 4 fma          -> 5 + 4 = 9 slots
-# and of the textbook form 1 exp + 1 rcp + full-rate ops: 13 and 18 slots.
-SLOTS_ISSUED = {"score": 6.0, "recompute": 9.0}
-SLOTS_CANONICAL = {"score": 13.0, "recompute": 18.0}
+# Issue slots per tanh evaluation of the two hot loops as written:
+#   forward score loop   fma, rcp, fma        -> 2 + 4 = 6 slots
+#   recompute loop       fma, rcp, 4 fma      -> 5 + 4 = 9 slots
+# and of the textbook form (add, exp, add, rcp, ... = 1 exp + 1 rcp + full-rate ops): 13 and 18 slots.
+SLOTS_ISSUED = {"fwd_fused": 6.0, "recompute": 9.0}
+SLOTS_CANONICAL = {"fwd_fused": 13.0, "recompute": 18.0}
+CAL_MIX = {"fwd_fused": "fwd_mix_tanh_per_s", "recompute": "bwd_mix_tanh_per_s"}
+# HBM bytes per launch (fetch + write) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the
+# same counters read for the library's plain copy kernel; source: profiles/bench_cfg1_kernels_and_counters.txt
+TRAFFIC_FROM_PROFILE = {"cfg1_nmt_f32_B64_T50_H512": {"fwd_fused": 15.8e6 + 7.2e6, "recompute": 16.1e6 + 13.2e6}}
 
 
 def main() -> int:
@@ -119,29 +124,35 @@ def main() -> int:
     # ---- machine ceilings measured here
     cal = calibrate(eb, torch, dev)
 
+    def alu_roofline(name):
+        us = kernels[name]["avg_us"]
+        slots = SLOTS_ISSUED[name] * n4u
+        achieved = 2 * slots / (us * 1e-6) / 1e12
+        mix = cal.get(CAL_MIX[name])
+        return {
+            "kernel": name, "bound": "alu", "achieved": achieved, "peak": PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": achieved / PEAK_TFLOPS,
+            "traffic": TRAFFIC_FROM_PROFILE.get(wl.name, {}).get(name),
+            "avg_launch_us": us, "tanh_evals_per_launch": n4u,
+            "slots_per_tanh_issued": SLOTS_ISSUED[name],
+            "frac_canonical_form": 2 * SLOTS_CANONICAL[name] * n4u / (us * 1e-6) / 1e12 / PEAK_TFLOPS,
+            "frac_of_measured_mix_ceiling": (n4u / (us * 1e-6)) / mix if mix else None,
+        }
+
     dom_us = kernels[dominant]["avg_us"]
     if dominant in SLOTS_ISSUED:
-        slots = SLOTS_ISSUED[dominant] * n4u
-        achieved = slots / (dom_us * 1e-6)
-        mix = cal["fwd_mix_tanh_per_s"] if dominant == "score" else cal["bwd_mix_tanh_per_s"]
-        roofline = {
-            "kernel": dominant, "bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_LANEOPS / 1e12,
-            "unit": "Tlaneop/s", "frac": achieved / PEAK_LANEOPS, "traffic": None,
-            "avg_launch_us": dom_us, "tanh_evals_per_launch": n4u,
-            "slots_per_tanh_issued": SLOTS_ISSUED[dominant],
-            "frac_canonical_form": SLOTS_CANONICAL[dominant] * n4u / (dom_us * 1e-6) / PEAK_LANEOPS,
-            "frac_of_measured_mix_ceiling": (n4u / (dom_us * 1e-6)) / mix if mix else None,
-        }
+        roofline = alu_roofline(dominant)
     else:
         roofline = {"kernel": dominant, "bound": "hbm", "achieved": None, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
                     "frac": None, "traffic": None, "avg_launch_us": dom_us}
+    hot_rooflines = {k: alu_roofline(k) for k in SLOTS_ISSUED if k in kernels}
 
     # end-to-end roofline time: arithmetic slots of both hot loops against the HBM minimum
     s_in = 2 if wl.in_dtype == "bf16" else 4
     io_bytes = ((wl.B * wl.Tq * wl.H + wl.B * wl.Tk * wl.H + wl.B * wl.Tk * wl.Dv) * s_in * 2   # fwd + bwd reads
                 + 4 * (wl.B * wl.Tq * wl.Dv * 2 + wl.B * wl.Tq * wl.Tk * 2)                      # C, dC, P w+r
                 + 4 * (wl.B * wl.Tq * wl.H + wl.B * wl.Tk * wl.H + wl.B * wl.Tk * wl.Dv))         # dQp, dKp, dV
-    t_alu = (SLOTS_ISSUED["score"] + SLOTS_ISSUED["recompute"]) * n4u / PEAK_LANEOPS
+    t_alu = (SLOTS_ISSUED["fwd_fused"] + SLOTS_ISSUED["recompute"]) * n4u / PEAK_SLOTS
     t_hbm = io_bytes / PEAK_HBM
     end_to_end = {"t_alu_us": t_alu * 1e6, "t_hbm_us": t_hbm * 1e6, "io_bytes": io_bytes,
                   "frac": max(t_alu, t_hbm) / (ms_per_step_events * 1e-3)}
@@ -185,6 +196,7 @@ def main() -> int:
         "ms_per_step_events": ms_per_step_events, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
         "kernels": kernels,
         "roofline": roofline,
+        "hot_kernel_rooflines": hot_rooflines,
         "end_to_end_roofline": end_to_end,
         "measured_ceilings": cal,
         "peak_bytes": peak,
