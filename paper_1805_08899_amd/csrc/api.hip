@@ -136,12 +136,11 @@ echo_status_t bwd_impl(const echo_attn_desc_t *desc, const float *dContext, cons
     float *rowsum = reinterpret_cast<float *>(ws + lay.rowsum_off);
     float *dv_part = reinterpret_cast<float *>(ws + lay.dvpart_off);
     int *order = reinterpret_cast<int *>(ws + lay.order_off);
-    ECHO_LAUNCH("dvalue", echo::launch_dvalue(s, P, dContext, key_len, dV, st));
-    ECHO_LAUNCH("dscore", echo::launch_dscore(s, dContext, V, P, key_len, dS, rowsum, order, st));
+    ECHO_LAUNCH("bwd_pre", echo::launch_bwd_pre(s, dContext, V, P, key_len, dS, rowsum, order, dV, st));
     ECHO_LAUNCH(use_map ? "recompute_stash" : "recompute",
-                echo::launch_recompute(s, Qp, Kp, v, key_len, order, dS, use_map ? tmap : nullptr, dQp, dKp, dv_part,
+                echo::launch_recompute(s, Qp, Kp, v, order, dS, rowsum, use_map ? tmap : nullptr, dQp, dKp, dv_part,
                                        st));
-    ECHO_LAUNCH("dv_reduce", echo::launch_dv_reduce(s, dv_part, rowsum, dv, st));
+    ECHO_LAUNCH("dv_reduce", echo::launch_dv_reduce(s, dv_part, dv, st));
     return ECHO_OK;
 }
 

@@ -26,17 +26,16 @@ __device__ __forceinline__ f32x4 mfma16(float a, float b, f32x4 c) {
 // output columns of tile c are n0 + 4*(l%16) + c and the store is 16 bytes too.
 // N must be a multiple of 4.
 template <typename TB, bool TRANS_A>
-__global__ __launch_bounds__(256) void k_pv(const float *__restrict__ P, const TB *__restrict__ Bm,
-                                            const int *__restrict__ key_len, float *__restrict__ out,
-                                            int Tq, int Tk, int N) {
-    const int b = blockIdx.z;
+__device__ __forceinline__ void pv_block(const float *__restrict__ P, const TB *__restrict__ Bm,
+                                         const int *__restrict__ key_len, float *__restrict__ out,
+                                         int Tq, int Tk, int N, int b, int by, int bx) {
     const int L = clamp_len(key_len[b], Tk);
     const int lane = lane_id(), w = wave_id();
     const int M = TRANS_A ? Tk : Tq;
     const int K = TRANS_A ? Tq : L;
     const int Mvalid = TRANS_A ? L : Tq;      // rows that can be non-zero
-    const int m0 = blockIdx.y * 16;
-    const int n0 = (blockIdx.x * 4 + w) * 64;
+    const int m0 = by * 16;
+    const int n0 = (bx * 4 + w) * 64;
     if (n0 >= N) return;
     const int lm = lane & 15, lk = lane >> 4;
     const int ncol = n0 + 4 * lm;             // first of this lane's four columns
@@ -87,6 +86,13 @@ __global__ __launch_bounds__(256) void k_pv(const float *__restrict__ P, const T
     }
 }
 
+template <typename TB, bool TRANS_A>
+__global__ __launch_bounds__(256) void k_pv(const float *__restrict__ P, const TB *__restrict__ Bm,
+                                            const int *__restrict__ key_len, float *__restrict__ out,
+                                            int Tq, int Tk, int N) {
+    pv_block<TB, TRANS_A>(P, Bm, key_len, out, Tq, Tk, N, blockIdx.z, blockIdx.y, blockIdx.x);
+}
+
 hipError_t launch_context(const AttnShape &s, const float *P, const void *V, const int *key_len, float *C,
                           hipStream_t st) {
     dim3 grid((s.Dv + 255) / 256, (s.Tq + 15) / 16, s.B);
@@ -97,15 +103,8 @@ hipError_t launch_context(const AttnShape &s, const float *P, const void *V, con
     return hipGetLastError();
 }
 
-hipError_t launch_dvalue(const AttnShape &s, const float *P, const float *dC, const int *key_len, float *dV,
-                         hipStream_t st) {
-    dim3 grid((s.Dv + 255) / 256, (s.Tk + 15) / 16, s.B);
-    k_pv<float, true><<<grid, 256, 0, st>>>(P, dC, key_len, dV, s.Tq, s.Tk, s.Dv);
-    return hipGetLastError();
-}
-
 // ---------------------------------------------------------------------------
-// Block = (b, 16 query rows).  Waves take key tiles of 16 in turn and compute
+// dS for (b, 16 query rows).  Waves take key tiles of 16 in turn and compute
 // dP[i, j] = sum_d dC[i, d] V[j, d] into LDS; then each wave finishes four
 // rows: r = sum_j P dP, dS = P (dP - r).  dS rows have pitch `pitch` floats and
 // are zero at j >= L_b (pads included).  Dv must be a multiple of 4.
@@ -113,32 +112,11 @@ hipError_t launch_dvalue(const AttnShape &s, const float *P, const float *dC, co
 // them on four MFMA steps, so the k index of step c is d0 + 4*(l/16) + c on
 // both sides.
 template <typename TV>
-__global__ __launch_bounds__(256) void k_dscore(const float *__restrict__ dC, const TV *__restrict__ V,
-                                                const float *__restrict__ P, const int *__restrict__ key_len,
-                                                float *__restrict__ dS, float *__restrict__ ds_rowsum,
-                                                int *__restrict__ order, int B, int sorted, int fold,
-                                                int Tq, int Tk, int Dv, int pitch) {
-    extern __shared__ float s_dp[];           // [16][pitch16]
-    const int b = blockIdx.y;
-    if (order && blockIdx.x == 0 && blockIdx.y == 0) {
-        // for the recompute kernel: samples ordered by valid keys, most first (ties by index)
-        for (int cand = threadIdx.x; cand < B; cand += 256) {
-            int r = cand;
-            if (sorted) {
-                const int lc = clamp_len(key_len[cand], Tk);
-                r = 0;
-                for (int o = 0; o < B; ++o) {
-                    const int lo = clamp_len(key_len[o], Tk);
-                    r += (lo > lc) || (lo == lc && o < cand);
-                }
-            }
-            // fold: when the whole grid is resident at once, blocks y and y + B/2 meet on one CU
-            // (two blocks per CU, placed in launch order), so the second half runs lightest first
-            const int half = (B + 1) / 2;
-            order[(fold && r >= half) ? half + (B - 1 - r) : r] = cand;
-        }
-    }
-    const int i0 = blockIdx.x * 16;
+__device__ __forceinline__ void dscore_block(const float *__restrict__ dC, const TV *__restrict__ V,
+                                             const float *__restrict__ P, const int *__restrict__ key_len,
+                                             float *__restrict__ dS, float *__restrict__ ds_rowsum,
+                                             float *__restrict__ s_dp, int b, int i0, int Tq, int Tk, int Dv,
+                                             int pitch) {
     const int L = clamp_len(key_len[b], Tk);
     const int lane = lane_id(), w = wave_id();
     const int lm = lane & 15, lk = lane >> 4;
@@ -200,26 +178,87 @@ __global__ __launch_bounds__(256) void k_dscore(const float *__restrict__ dC, co
     }
 }
 
-hipError_t launch_dscore(const AttnShape &s, const float *dC, const void *V, const float *P, const int *key_len,
-                         float *dS, float *ds_rowsum, int *order, hipStream_t st) {
+// For the recompute kernel: order[r] = b | L_b << 16 for the sample b with the
+// r-th most valid keys (ties by index), or r-th in index order when `sorted` is 0.  With `fold` the second
+// half runs lightest first: when the whole recompute grid is resident at once,
+// blocks y and y + B/2 meet on one CU (two blocks per CU, placed in launch
+// order), so heavy samples are paired with light ones.
+__device__ __forceinline__ void rank_block(const int *__restrict__ key_len, int *__restrict__ order,
+                                           int *__restrict__ s_len, int B, int Tk, int sorted, int fold) {
+    if (sorted)
+        for (int o = threadIdx.x; o < B; o += 256) s_len[o] = clamp_len(key_len[o], Tk);
+    __syncthreads();
+    const int half = (B + 1) / 2;
+    for (int cand = threadIdx.x; cand < B; cand += 256) {
+        int r = cand;
+        const int lc = sorted ? s_len[cand] : clamp_len(key_len[cand], Tk);
+        if (sorted) {
+            r = 0;
+            for (int o = 0; o < B; ++o) {
+                const int lo = s_len[o];
+                r += (lo > lc) || (lo == lc && o < cand);
+            }
+        }
+        order[(fold && r >= half) ? half + (B - 1 - r) : r] = cand | (lc << 16);
+    }
+}
+
+// Everything the backward pass needs before the recomputation, in one launch:
+// block 0 ranks the samples, the next nS blocks produce dS (B1 + B2), the
+// rest produce dV (B1).  The three kinds of block do not depend on each other.
+template <typename TV>
+__global__ __launch_bounds__(256) void k_bwd_pre(const float *__restrict__ dC, const TV *__restrict__ V,
+                                                 const float *__restrict__ P, const int *__restrict__ key_len,
+                                                 float *__restrict__ dS, float *__restrict__ ds_rowsum,
+                                                 int *__restrict__ order, float *__restrict__ dV, int B, int sorted,
+                                                 int fold,
+                                                 int Tq, int Tk, int Dv, int pitch, int s_tiles, int v_xt, int v_yt) {
+    extern __shared__ float s_dp[];           // [16][pitch16]
+    __shared__ int s_len[kMaxSortedB];
+    int bid = blockIdx.x;
+    if (bid == 0) {
+        rank_block(key_len, order, s_len, B, Tk, sorted, fold);
+        return;
+    }
+    bid -= 1;
+    const int nS = s_tiles * B;
+    if (bid < nS) {
+        dscore_block<TV>(dC, V, P, key_len, dS, ds_rowsum, s_dp, bid / s_tiles, (bid % s_tiles) * 16, Tq, Tk, Dv,
+                         pitch);
+        return;
+    }
+    bid -= nS;
+    const int per_b = v_xt * v_yt;
+    const int b = bid / per_b, rem = bid % per_b;
+    pv_block<float, true>(P, dC, key_len, dV, Tq, Tk, Dv, b, rem / v_xt, rem % v_xt);
+}
+
+hipError_t launch_bwd_pre(const AttnShape &s, const float *dC, const void *V, const float *P, const int *key_len,
+                          float *dS, float *ds_rowsum, int *order, float *dV, hipStream_t st) {
     const int sorted = s.B <= kMaxSortedB ? 1 : 0;
-    const int fold = (sorted && (long long)s.B * ((s.H + 63) / 64) <= 512) ? 1 : 0;   // recompute grid in one round
-    dim3 grid((s.Tq + 15) / 16, s.B);
+    const int n_hs = (s.H + 63) / 64;
+    const int fold = (sorted && (long long)s.B * n_hs <= 512) ? 1 : 0;   // recompute grid in one round
+    const int s_tiles = (s.Tq + 15) / 16;
+    const int v_xt = (s.Dv + 255) / 256, v_yt = (s.Tk + 15) / 16;
+    const long long blocks = 1 + (long long)s.B * s_tiles + (long long)s.B * v_xt * v_yt;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     const int pitch16 = (s.Tk + 15) / 16 * 16 + 4;
     const size_t lds = (size_t)16 * pitch16 * sizeof(float);
     if (lds > 48 * 1024) {   // beyond the default dynamic LDS limit: raise it (up to 160 KB per block on gfx950)
-        hipError_t e = s.bf16 ? hipFuncSetAttribute((const void *)k_dscore<bf16_t>,
+        hipError_t e = s.bf16 ? hipFuncSetAttribute((const void *)k_bwd_pre<bf16_t>,
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
-                              : hipFuncSetAttribute((const void *)k_dscore<float>,
+                              : hipFuncSetAttribute((const void *)k_bwd_pre<float>,
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
     if (s.bf16)
-        k_dscore<bf16_t><<<grid, 256, lds, st>>>(dC, (const bf16_t *)V, P, key_len, dS, ds_rowsum, order, s.B, sorted, fold,
-                                                 s.Tq, s.Tk, s.Dv, ds_pitch(s.Tk));
+        k_bwd_pre<bf16_t><<<(unsigned)blocks, 256, lds, st>>>(dC, (const bf16_t *)V, P, key_len, dS, ds_rowsum, order,
+                                                             dV, s.B, sorted, fold, s.Tq, s.Tk, s.Dv,
+                                                             ds_pitch(s.Tk), s_tiles, v_xt, v_yt);
     else
-        k_dscore<float><<<grid, 256, lds, st>>>(dC, (const float *)V, P, key_len, dS, ds_rowsum, order, s.B, sorted, fold,
-                                                s.Tq, s.Tk, s.Dv, ds_pitch(s.Tk));
+        k_bwd_pre<float><<<(unsigned)blocks, 256, lds, st>>>(dC, (const float *)V, P, key_len, dS, ds_rowsum, order,
+                                                            dV, s.B, sorted, fold, s.Tq, s.Tk, s.Dv,
+                                                            ds_pitch(s.Tk), s_tiles, v_xt, v_yt);
     return hipGetLastError();
 }
 

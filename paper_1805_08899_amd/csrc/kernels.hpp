@@ -28,23 +28,19 @@ hipError_t launch_softmax(const AttnShape &s, const float *S, const int *key_len
 // F3  context = P . V            (MFMA)
 hipError_t launch_context(const AttnShape &s, const float *P, const void *V, const int *key_len, float *C,
                           hipStream_t st);
-// B1  dV = P^T . dC              (MFMA)
-hipError_t launch_dvalue(const AttnShape &s, const float *P, const float *dC, const int *key_len, float *dV,
-                         hipStream_t st);
-// B1+B2  dP = dC . V^T (MFMA) then dS = P (dP - rowsum(P dP)); dS has row pitch ds_pitch(Tk);
-// ds_rowsum[b*Tq+i] = sum_j dS
-// order[r] = sample with the r-th most valid keys (written when order != nullptr; identity if B > kMaxSortedB)
+// B1 + B2 and the sample ranking in one launch:
+//   dV = P^T . dC (MFMA);  dP = dC . V^T (MFMA) then dS = P (dP - rowsum(P dP)), dS has row pitch ds_pitch(Tk),
+//   ds_rowsum[b*Tq+i] = sum_j dS;
+//   order[r] = b | L_b << 16 for the sample with the r-th most valid keys (index order if B > kMaxSortedB)
 constexpr int kMaxSortedB = 1024;
-hipError_t launch_dscore(const AttnShape &s, const float *dC, const void *V, const float *P, const int *key_len,
-                         float *dS, float *ds_rowsum, int *order, hipStream_t st);
-// B3  fused recompute: dQp, dKp, per-sample partials of dv  (dv_part [B,H]);
+hipError_t launch_bwd_pre(const AttnShape &s, const float *dC, const void *V, const float *P, const int *key_len,
+                          float *dS, float *ds_rowsum, int *order, float *dV, hipStream_t st);
+// B3  fused recompute: dQp, dKp, per-sample partials of dv (dv_part [B,H]);
 // tmap != nullptr reads tanh from the stashed map instead of recomputing it
-// order (may be nullptr) maps blockIdx.y to the sample it works on
-hipError_t launch_recompute(const AttnShape &s, const void *Qp, const void *Kp, const void *v, const int *key_len,
-                            const int *order, const float *dS, const float *tmap, float *dQp, float *dKp,
+hipError_t launch_recompute(const AttnShape &s, const void *Qp, const void *Kp, const void *v, const int *order,
+                            const float *dS, const float *ds_rowsum, const float *tmap, float *dQp, float *dKp,
                             float *dv_part, hipStream_t st);
-// B4  dv[h] = sum_b dv_part[b,h] + sum ds_rowsum, fixed order
-hipError_t launch_dv_reduce(const AttnShape &s, const float *dv_part, const float *ds_rowsum, float *dv,
-                            hipStream_t st);
+// B4  dv[h] = sum_b dv_part[b,h], fixed order
+hipError_t launch_dv_reduce(const AttnShape &s, const float *dv_part, float *dv, hipStream_t st);
 
 }  // namespace echo

@@ -82,7 +82,7 @@ __device__ __forceinline__ void rc_tile_n(int ni, const float (&fq)[RC_RI], cons
 template <typename T, bool STASH>
 __global__ __launch_bounds__(RC_THREADS) void k_recompute(
     const T *__restrict__ Qp, const T *__restrict__ Kp, const T *__restrict__ v,
-    const int *__restrict__ key_len, const int *__restrict__ order, const float *__restrict__ dS,
+    const int *__restrict__ order, const float *__restrict__ dS, const float *__restrict__ ds_rowsum,
     const float *__restrict__ tmap, float *__restrict__ dQp, float *__restrict__ dKp, float *__restrict__ dv_part,
     int Tq, int Tk, int H, int pitch, int rows_per_pass) {
     // Key tile staged once per block, double buffered: exp(2k) for the factor
@@ -93,13 +93,15 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
     __shared__ float s_ds[2][RC_THREADS];     // dS of the pass rows x tile keys, [row][key]
     __shared__ float s_part[2][RC_W][RC_RJ][64];
     __shared__ float s_dv[RC_W][64];
+    __shared__ float s_rowsum;
 
-    const int b = order ? order[blockIdx.y] : blockIdx.y;     // samples with the most valid keys start first
+    // slot -> sample (the heaviest samples start first) and its clamped key length, packed by the ranking block
+    const int packed = order[blockIdx.y];
+    const int b = packed & 0xffff, L = packed >> 16;
     const int lane = lane_id(), w = wave_id();
     const int h = blockIdx.x * 64 + lane;
     const bool hv = h < H;
     const int hc = hv ? h : H - 1;
-    const int L = clamp_len(key_len[b], Tk);
     const float vh = hv ? ld(v, hc) : 0.f;
     const float v4 = 4.f * vh;
 
@@ -112,154 +114,163 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
     if (L == 0) {                                   // block-uniform
         for (int i = w; i < Tq; i += RC_W)
             if (hv) dQb[(size_t)i * H + h] = 0.f;
-        if (w == 0 && hv) dv_part[(size_t)b * H + h] = 0.f;
-        return;
+    }
+    if (w == RC_W - 1) {
+        // sum of this sample's dS (zero in exact arithmetic): the part of sum dS t that comes from t = 1 - 2r
+        float rs = 0.f;
+        for (int i = lane; i < Tq; i += 64) rs += ds_rowsum[(size_t)b * Tq + i];
+        rs = wave_sum(rs);
+        if (lane == 0) s_rowsum = rs;
     }
 
-    const T *qb = Qp + (size_t)b * Tq * H;
-    const T *kb = Kp + (size_t)b * Tk * H;
-    const float *dsb = dS + (size_t)b * Tq * pitch;
-    const int n_jt = (L + RC_RJ - 1) / RC_RJ;
     float accV = 0.f;
+    if (L > 0) {
+        const T *qb = Qp + (size_t)b * Tq * H;
+        const T *kb = Kp + (size_t)b * Tk * H;
+        const float *dsb = dS + (size_t)b * Tq * pitch;
+        const int n_jt = (L + RC_RJ - 1) / RC_RJ;
 
-    // Tile staging, one tile ahead of the arithmetic.  Wave w fetches key w of the
-    // tile (RC_W == RC_RJ) and thread t the dS element (row t / 8, key t % 8) of
-    // the pass; the loads are issued before the current tile is evaluated and
-    // committed to the other LDS buffer after it.
-    const int t_row = threadIdx.x / RC_RJ, t_col = threadIdx.x % RC_RJ;
-    float kx = 0.f, dx = 0.f;
-    auto fetch = [&](int jt, int i_pass0, int nrows) {
-        const int j = jt * RC_RJ + w;
-        kx = (!STASH && j < L) ? ld(kb, (size_t)j * H + hc) : 0.f;
-        dx = (t_row < nrows) ? dsb[(size_t)(i_pass0 + t_row) * pitch + jt * RC_RJ + t_col] : 0.f;
-    };
-    auto commit = [&](int jt, int buf) {
-        const int j = jt * RC_RJ + w;
-        s_ds[buf][threadIdx.x] = dx;
-        if (STASH) return;
-        s_sk[buf][w][lane] = kTwoLog2e * kx;
-        s_fk[buf][w][lane] = (j < L) ? fast_exp2(kTwoLog2e * kx) : 0.f;
-        const int big = __any(fabsf(kx) > kFactorLimit) ? 1 : 0;
-        if (lane == 0) s_kbig[buf][w] = big;
-    };
+        // Tile staging, one tile ahead of the arithmetic.  Wave w fetches key w of the
+        // tile (RC_W == RC_RJ) and thread t the dS element (row t / 8, key t % 8) of
+        // the pass; the loads are issued before the current tile is evaluated and
+        // committed to the other LDS buffer after it.
+        const int t_row = threadIdx.x / RC_RJ, t_col = threadIdx.x % RC_RJ;
+        float kx = 0.f, dx = 0.f;
+        auto fetch = [&](int jt, int i_pass0, int nrows) {
+            const int j = jt * RC_RJ + w;
+            kx = (!STASH && j < L) ? ld(kb, (size_t)j * H + hc) : 0.f;
+            dx = (t_row < nrows) ? dsb[(size_t)(i_pass0 + t_row) * pitch + jt * RC_RJ + t_col] : 0.f;
+        };
+        auto commit = [&](int jt, int buf) {
+            const int j = jt * RC_RJ + w;
+            s_ds[buf][threadIdx.x] = dx;
+            if (STASH) return;
+            s_sk[buf][w][lane] = kTwoLog2e * kx;
+            s_fk[buf][w][lane] = (j < L) ? fast_exp2(kTwoLog2e * kx) : 0.f;
+            const int big = __any(fabsf(kx) > kFactorLimit) ? 1 : 0;
+            if (lane == 0) s_kbig[buf][w] = big;
+        };
 
-    int pass = 0;
-    for (int i_pass0 = 0; i_pass0 < Tq; i_pass0 += rows_per_pass, ++pass) {
-        const int nrows = min(rows_per_pass, Tq - i_pass0);
-        const int r_lo = (nrows * w) / RC_W, r_hi = (nrows * (w + 1)) / RC_W;
-        const int ni = r_hi - r_lo;              // 0..RC_RI
-        const int i0 = i_pass0 + r_lo;
+        int pass = 0;
+        for (int i_pass0 = 0; i_pass0 < Tq; i_pass0 += rows_per_pass, ++pass) {
+            const int nrows = min(rows_per_pass, Tq - i_pass0);
+            const int r_lo = (nrows * w) / RC_W, r_hi = (nrows * (w + 1)) / RC_W;
+            const int ni = r_hi - r_lo;              // 0..RC_RI
+            const int i0 = i_pass0 + r_lo;
 
-        fetch(0, i_pass0, nrows);
-        float fq[RC_RI], sq[RC_RI], accQ[RC_RI];
-        bool qbig = false;
-        {
-            float x[RC_RI];
+            fetch(0, i_pass0, nrows);
+            float fq[RC_RI], sq[RC_RI], accQ[RC_RI];
+            bool qbig = false;
+            {
+                float x[RC_RI];
 #pragma unroll
-            for (int a = 0; a < RC_RI; ++a) x[a] = (!STASH && a < ni) ? ld(qb, (size_t)(i0 + a) * H + hc) : 0.f;
+                for (int a = 0; a < RC_RI; ++a) x[a] = (!STASH && a < ni) ? ld(qb, (size_t)(i0 + a) * H + hc) : 0.f;
 #pragma unroll
-            for (int a = 0; a < RC_RI; ++a) {
-                accQ[a] = 0.f;
-                qbig |= fabsf(x[a]) > kFactorLimit;
-                sq[a] = kTwoLog2e * x[a];
-                fq[a] = fast_exp2(sq[a]);
-            }
-        }
-        const bool wave_qbig = __any(qbig);
-        commit(0, 0);
-        __syncthreads();
-
-        for (int jt = 0; jt < n_jt; ++jt) {
-            const int buf = jt & 1;
-            const int j0 = jt * RC_RJ;
-            const bool more = jt + 1 < n_jt;
-            if (more) fetch(jt + 1, i_pass0, nrows);
-            float accK[RC_RJ], fk[RC_RJ];
-            int kcol[RC_RJ];
-#pragma unroll
-            for (int c = 0; c < RC_RJ; ++c) {
-                accK[c] = 0.f;
-                kcol[c] = min(j0 + c, L - 1);
-            }
-            const float *ds_tile = &s_ds[buf][r_lo * RC_RJ];     // wave-uniform reads, pitch RC_RJ
-            if (STASH) {
-                const float *t_tile = tmap + (((size_t)b * Tq + i0) * Tk) * H + hc;
-#pragma unroll
-                for (int c = 0; c < RC_RJ; ++c) fk[c] = 0.f;
-                rc_tile_n<RC_STASH>(ni, fq, fk, ds_tile, RC_RJ, t_tile, (size_t)Tk * H, (size_t)H, kcol, accQ, accK,
-                                    accV);
-            } else {
-                int kbig = 0;
-#pragma unroll
-                for (int c = 0; c < RC_RJ; ++c) kbig |= s_kbig[buf][c];
-                if (!(wave_qbig || kbig)) {
-#pragma unroll
-                    for (int c = 0; c < RC_RJ; ++c) fk[c] = s_fk[buf][c][lane];
-                    rc_tile_n<RC_FACTOR>(ni, fq, fk, ds_tile, RC_RJ, nullptr, 0, 0, kcol, accQ, accK, accV);
-                } else {
-#pragma unroll
-                    for (int c = 0; c < RC_RJ; ++c) fk[c] = s_sk[buf][c][lane];
-                    rc_tile_n<RC_EXACT>(ni, sq, fk, ds_tile, RC_RJ, nullptr, 0, 0, kcol, accQ, accK, accV);
+                for (int a = 0; a < RC_RI; ++a) {
+                    accQ[a] = 0.f;
+                    qbig |= fabsf(x[a]) > kFactorLimit;
+                    sq[a] = kTwoLog2e * x[a];
+                    fq[a] = fast_exp2(sq[a]);
                 }
             }
-            if (more) commit(jt + 1, buf ^ 1);
-#pragma unroll
-            for (int c = 0; c < RC_RJ; ++c) s_part[buf][w][c][lane] = accK[c];
+            const bool wave_qbig = __any(qbig);
+            commit(0, 0);
             __syncthreads();
-            // wave w finishes key j0 + w of this tile: sum over the waves in fixed order
-            const int j = j0 + w;
-            float tot = 0.f;
+
+            for (int jt = 0; jt < n_jt; ++jt) {
+                const int buf = jt & 1;
+                const int j0 = jt * RC_RJ;
+                const bool more = jt + 1 < n_jt;
+                if (more) fetch(jt + 1, i_pass0, nrows);
+                float accK[RC_RJ], fk[RC_RJ];
+                int kcol[RC_RJ];
 #pragma unroll
-            for (int w2 = 0; w2 < RC_W; ++w2) tot += s_part[buf][w2][w][lane];
-            if (j < L && hv) {
-                float *dst = dKb + (size_t)j * H + h;
-                const float val = v4 * tot;
-                *dst = (pass == 0) ? val : *dst + val;
+                for (int c = 0; c < RC_RJ; ++c) {
+                    accK[c] = 0.f;
+                    kcol[c] = min(j0 + c, L - 1);
+                }
+                const float *ds_tile = &s_ds[buf][r_lo * RC_RJ];     // wave-uniform reads, pitch RC_RJ
+                if (STASH) {
+                    const float *t_tile = tmap + (((size_t)b * Tq + i0) * Tk) * H + hc;
+#pragma unroll
+                    for (int c = 0; c < RC_RJ; ++c) fk[c] = 0.f;
+                    rc_tile_n<RC_STASH>(ni, fq, fk, ds_tile, RC_RJ, t_tile, (size_t)Tk * H, (size_t)H, kcol, accQ, accK,
+                                        accV);
+                } else {
+                    int kbig = 0;
+#pragma unroll
+                    for (int c = 0; c < RC_RJ; ++c) kbig |= s_kbig[buf][c];
+                    if (!(wave_qbig || kbig)) {
+#pragma unroll
+                        for (int c = 0; c < RC_RJ; ++c) fk[c] = s_fk[buf][c][lane];
+                        rc_tile_n<RC_FACTOR>(ni, fq, fk, ds_tile, RC_RJ, nullptr, 0, 0, kcol, accQ, accK, accV);
+                    } else {
+#pragma unroll
+                        for (int c = 0; c < RC_RJ; ++c) fk[c] = s_sk[buf][c][lane];
+                        rc_tile_n<RC_EXACT>(ni, sq, fk, ds_tile, RC_RJ, nullptr, 0, 0, kcol, accQ, accK, accV);
+                    }
+                }
+                if (more) commit(jt + 1, buf ^ 1);
+#pragma unroll
+                for (int c = 0; c < RC_RJ; ++c) s_part[buf][w][c][lane] = accK[c];
+                __syncthreads();
+                // wave w finishes key j0 + w of this tile: sum over the waves in fixed order
+                const int j = j0 + w;
+                float tot = 0.f;
+#pragma unroll
+                for (int w2 = 0; w2 < RC_W; ++w2) tot += s_part[buf][w2][w][lane];
+                if (j < L && hv) {
+                    float *dst = dKb + (size_t)j * H + h;
+                    const float val = v4 * tot;
+                    *dst = (pass == 0) ? val : *dst + val;
+                }
             }
-        }
-        if (hv) {
+            if (hv) {
 #pragma unroll
-            for (int a = 0; a < RC_RI; ++a)
-                if (a < ni) dQb[(size_t)(i0 + a) * H + h] = v4 * accQ[a];
+                for (int a = 0; a < RC_RI; ++a)
+                    if (a < ni) dQb[(size_t)(i0 + a) * H + h] = v4 * accQ[a];
+            }
+            __syncthreads();   // the next pass restages buffer 0 and reuses s_part
         }
-        __syncthreads();   // the next pass restages buffer 0 and reuses s_part
     }
 
-    // dv partial of this sample: sum dS t = sum dS - 2 sum dS r; the first term is added by the final reduction
+    // dv partial of this sample: sum dS t = sum dS - 2 sum dS r
     s_dv[w][lane] = accV;
     __syncthreads();
-    if (w == 0 && hv) {
-        float tot = 0.f;
+    if (w == 0) {
+        if (hv) {
+            float tot = 0.f;
 #pragma unroll
-        for (int w2 = 0; w2 < RC_W; ++w2) tot += s_dv[w2][lane];
-        dv_part[(size_t)b * H + h] = -2.f * tot;
+            for (int w2 = 0; w2 < RC_W; ++w2) tot += s_dv[w2][lane];
+            dv_part[(size_t)b * H + h] = __builtin_fmaf(-2.f, tot, s_rowsum);
+        }
     }
 }
 
 template <typename T>
 static hipError_t launch_recompute_t(const AttnShape &s, const void *Qp, const void *Kp, const void *v,
-                                     const int *key_len, const int *order, const float *dS, const float *tmap,
+                                     const int *order, const float *dS, const float *ds_rowsum, const float *tmap,
                                      float *dQp, float *dKp, float *dv_part, hipStream_t st) {
     const int max_rows = RC_W * RC_RI;
     const int n_pass = (s.Tq + max_rows - 1) / max_rows;
     const int rows_per_pass = (s.Tq + n_pass - 1) / n_pass;
     dim3 grid((s.H + 63) / 64, s.B);
     if (tmap)
-        k_recompute<T, true><<<grid, RC_THREADS, 0, st>>>((const T *)Qp, (const T *)Kp, (const T *)v, key_len, order,
-                                                          dS, tmap, dQp, dKp, dv_part, s.Tq, s.Tk, s.H,
+        k_recompute<T, true><<<grid, RC_THREADS, 0, st>>>((const T *)Qp, (const T *)Kp, (const T *)v, order, dS,
+                                                          ds_rowsum, tmap, dQp, dKp, dv_part, s.Tq, s.Tk, s.H,
                                                           ds_pitch(s.Tk), rows_per_pass);
     else
-        k_recompute<T, false><<<grid, RC_THREADS, 0, st>>>((const T *)Qp, (const T *)Kp, (const T *)v, key_len, order,
-                                                           dS, tmap, dQp, dKp, dv_part, s.Tq, s.Tk, s.H,
+        k_recompute<T, false><<<grid, RC_THREADS, 0, st>>>((const T *)Qp, (const T *)Kp, (const T *)v, order, dS,
+                                                           ds_rowsum, tmap, dQp, dKp, dv_part, s.Tq, s.Tk, s.H,
                                                            ds_pitch(s.Tk), rows_per_pass);
     return hipGetLastError();
 }
 
-hipError_t launch_recompute(const AttnShape &s, const void *Qp, const void *Kp, const void *v, const int *key_len,
-                            const int *order, const float *dS, const float *tmap, float *dQp, float *dKp,
+hipError_t launch_recompute(const AttnShape &s, const void *Qp, const void *Kp, const void *v, const int *order,
+                            const float *dS, const float *ds_rowsum, const float *tmap, float *dQp, float *dKp,
                             float *dv_part, hipStream_t st) {
-    return s.bf16 ? launch_recompute_t<bf16_t>(s, Qp, Kp, v, key_len, order, dS, tmap, dQp, dKp, dv_part, st)
-                  : launch_recompute_t<float>(s, Qp, Kp, v, key_len, order, dS, tmap, dQp, dKp, dv_part, st);
+    return s.bf16 ? launch_recompute_t<bf16_t>(s, Qp, Kp, v, order, dS, ds_rowsum, tmap, dQp, dKp, dv_part, st)
+                  : launch_recompute_t<float>(s, Qp, Kp, v, order, dS, ds_rowsum, tmap, dQp, dKp, dv_part, st);
 }
 
 }  // namespace echo

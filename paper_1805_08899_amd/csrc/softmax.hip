@@ -1,5 +1,6 @@
 // F2: masked softmax over the keys of one (b, i) row (attention weights,
-// Section 2 step 1), and B4: the fixed-order reduction that finishes dv.
+// Section 2 step 1), used when the forward pass is not fused; and B4: the
+// fixed-order reduction that finishes dv.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -34,52 +35,36 @@ hipError_t launch_softmax(const AttnShape &s, const float *S, const int *key_len
     return hipGetLastError();
 }
 
-// dv[h] = c0 + sum_b dv_part[b,h];  c0 = sum over all rows of ds_rowsum (the
-// part of sum dS*tanh that comes from tanh = 1 - 2r; it is zero in exact
-// arithmetic because every row of dS sums to zero).  Block = 64 values of h x
-// 4 groups of samples; every partial sum and the final combination run in a
-// fixed order, so the result is reproducible.
-__global__ __launch_bounds__(256) void k_dv_reduce(const float *__restrict__ dv_part,
-                                                  const float *__restrict__ ds_rowsum, float *__restrict__ dv,
-                                                  int B, int rows, int H) {
-    __shared__ float s_c0[256];
-    __shared__ float s_acc[4][64];
+// dv[h] = sum_b dv_part[b,h].  Block = 64 values of h x 8 groups of samples:
+// group g adds samples g, g + 8, ... with eight loads in flight at a time, then
+// the groups' sums are added in group order, so the result is reproducible.
+__global__ __launch_bounds__(512) void k_dv_reduce(const float *__restrict__ dv_part, float *__restrict__ dv, int B,
+                                                  int H) {
+    __shared__ float s_acc[8][64];
     const int lane = lane_id(), g = wave_id();
-    // loads go out eight at a time so that their latencies overlap
-    float c0 = 0.f;
-    for (int r0 = threadIdx.x; r0 < rows; r0 += 8 * 256) {
-        float x[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) x[u] = (r0 + u * 256 < rows) ? ds_rowsum[r0 + u * 256] : 0.f;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) c0 += x[u];
-    }
-    s_c0[threadIdx.x] = c0;
     const int h = blockIdx.x * 64 + lane;
     float acc = 0.f;
     if (h < H) {
-        for (int b0 = g; b0 < B; b0 += 8 * 4) {
+        for (int b0 = g; b0 < B; b0 += 8 * 8) {
             float x[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) x[u] = (b0 + 4 * u < B) ? dv_part[(size_t)(b0 + 4 * u) * H + h] : 0.f;
+            for (int u = 0; u < 8; ++u) x[u] = (b0 + 8 * u < B) ? dv_part[(size_t)(b0 + 8 * u) * H + h] : 0.f;
 #pragma unroll
             for (int u = 0; u < 8; ++u) acc += x[u];
         }
     }
     s_acc[g][lane] = acc;
     __syncthreads();
-    if (g == 0) {
-        float c = 0.f;
+    if (g == 0 && h < H) {
+        float tot = 0.f;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) c += s_c0[lane + 64 * k];
-        c = wave_sum(c);
-        if (h < H) dv[h] = ((s_acc[0][lane] + s_acc[1][lane]) + (s_acc[2][lane] + s_acc[3][lane])) + c;
+        for (int k = 0; k < 8; ++k) tot += s_acc[k][lane];
+        dv[h] = tot;
     }
 }
 
-hipError_t launch_dv_reduce(const AttnShape &s, const float *dv_part, const float *ds_rowsum, float *dv,
-                            hipStream_t st) {
-    k_dv_reduce<<<(s.H + 63) / 64, 256, 0, st>>>(dv_part, ds_rowsum, dv, s.B, s.B * s.Tq, s.H);
+hipError_t launch_dv_reduce(const AttnShape &s, const float *dv_part, float *dv, hipStream_t st) {
+    k_dv_reduce<<<(s.H + 63) / 64, 512, 0, st>>>(dv_part, dv, s.B, s.H);
     return hipGetLastError();
 }
 
