@@ -105,7 +105,7 @@ echo_status_t fwd_impl(const echo_attn_desc_t *desc, const void *Qp, const void 
     if (workspace_bytes < fwd_bytes(s)) return ECHO_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     float *S = static_cast<float *>(workspace);
-    if (!want_map && echo::fwd_fused_lds_bytes(s) <= 150 * 1024 && (size_t)s.B * sizeof(int) <= 64 * 1024) {
+    if (!want_map && echo::fwd_fused_supported(s)) {
         ECHO_LAUNCH("fwd_fused", echo::launch_fwd_fused(s, Qp, Kp, V, v, key_len, context, P, st));
         return ECHO_OK;
     }

@@ -3,34 +3,36 @@
 // (Section 2, attention steps 1-2; Section 4.1 scoring function; Section 6.1:
 // one fused kernel instead of many small ones, fewer launches and accesses).
 //
-// Block = (sample b, FW_R query rows), 8 waves, two blocks per CU.
+// Block = (sample b, up to RT = 8 NG query rows), 8 waves.
 //   A  exp(2q) of the rows goes to LDS (taken once per block).
-//   B  keys are dealt to the waves round-robin, FW_RJ per wave and chunk of 32;
-//      lanes run along h.  A wave loads its own key rows straight from memory
-//      (every K element is exponentiated once per block), evaluates its rows x
-//      keys register tile slice by slice of 64 h
+//   B  the valid keys are dealt to the waves in eight contiguous, equal shares;
+//      a wave walks its share in passes of up to four keys.  A lane owns four
+//      consecutive h of every 256-wide slice, so a key row arrives as one
+//      16-byte load per lane (every K element is exponentiated once per block)
+//      and a staged query row as one 16-byte LDS read.  Per row, key and h
 //          acc += v[h] * rcp(fma(exp(2q), exp(2k), 1))
-//      and finishes with one transposing wave reduction per tile.  A tile that
-//      met a pre-activation beyond the factorisation limit is redone by a
-//      small exact routine that exponentiates the sum.
-//   C  wave r normalises row r (softmax over the valid keys), writes P.
+//      and a pass finishes with one transposing wave reduction of its
+//      rows x keys tile.  A pass that met a pre-activation beyond the
+//      factorisation limit is redone by a small exact routine that
+//      exponentiates the sum.
+//   C  the waves normalise the rows (softmax over the valid keys) and write P.
 //   D  context = P V on the matrix cores: v_mfma_f32_4x4x1 treats the 64 lanes
 //      as 16 column groups of 4, so a lane owns one output column and reads V
 //      rows with plain coalesced loads.
 //
-// The whole pass of a block is short compared with a trip to memory, so every
-// phase issues its loads in batches before it consumes them: query rows and
-// the first key slices leave together, key slices run FW_PF ahead of the
-// arithmetic, and the first FW_KB value rows leave before the softmax.
+// A block's whole pass is short compared with a trip to memory, so loads are
+// issued well before they are consumed: the first key slice leaves before the
+// query rows are staged, key slices run one ahead of the arithmetic across
+// pass boundaries, and the first value rows leave before the softmax.
 //
-// Placement.  Two 8-wave blocks share a CU; the hardware hands blocks to the
-// XCDs round-robin and, while every block of the grid fits at once, block i
-// and block i + 256 land on the same CU.  The kernel ranks the samples by
-// valid keys, deals them to the XCDs in snake order (equal work per XCD, and
-// all tiles of a sample share one L2), and inside an XCD gives the CUs that
-// hold one block the heaviest tiles and pairs heavy with light tiles on the
-// others.  With more than two rounds of blocks it simply starts the heaviest
-// first.  The mapping only moves work around; results do not depend on it.
+// Placement.  The hardware hands blocks to the XCDs round-robin.  For small
+// batches every wave ranks the samples by valid keys itself (lengths in
+// registers, no LDS, no barrier), deals them to the XCDs in snake order (equal
+// work per XCD, all tiles of a sample share one L2) and, when two blocks share
+// a CU, gives the CUs that hold one block the heaviest tiles and pairs heavy
+// with light tiles on the others; with more rounds of blocks the heaviest
+// simply start first.  The mapping only moves work around; results do not
+// depend on it.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -48,89 +50,154 @@ __device__ long long g_stamps[16384 * 8];
 #define FW_STAMP(k)
 #endif
 
-constexpr int FW_R = 8;          // query rows per block (register tile rows)
-constexpr int FW_RJ = 4;         // keys per wave and chunk (register tile columns)
 constexpr int FW_W = 8;          // waves per block
-constexpr int FW_CHUNK = FW_W * FW_RJ;   // keys per chunk
 constexpr int FW_THREADS = 64 * FW_W;
+constexpr int FW_NJ = 4;         // keys per wave and pass (register tile columns)
+constexpr int FW_SS = 256;       // h per slice: four per lane
 constexpr int FW_XCD = 8;        // blockIdx.x mod 8 selects the XCD
 constexpr int FW_CU_PER_XCD = 32;
-constexpr int FW_PF = 4;         // slices of h whose key values are in flight per wave
-constexpr int FW_KB = 32;        // value rows in flight per wave in the context phase
-constexpr int FW_MAX_RANKED_B = 1024;   // the in-kernel ranking is quadratic in B
+constexpr int FW_KB = 16;        // value rows per batch in the context phase (two batches in flight per wave)
+constexpr int FW_MAX_RANKED_B = 128;   // the in-kernel ranking keeps two lengths per lane
 
-// One wave, NJ keys (rows krow0 + c*kstride), all slices of h, factor path only.  s_e: LDS rows of
-// exp(2q), pitch Hp (rows past ni hold zeros).  FULL: all FW_R rows are live, else the first ni.
-// kx[u][c] / vx[u] arrive holding slices 0..FW_PF-1 of the wave's keys and of v (invalid lanes of v
-// hold 0); the ring is rotated every slice and refilled FW_PF slices ahead.  Returns true if a key value was beyond the factor
-// limit, in which case nothing was written and the caller must redo the tile exactly.
-template <typename T, int NJ, bool FULL>
-__device__ __forceinline__ bool fw_score_wave(const float *__restrict__ s_e, int Hp, int ni,
-                                              const T *__restrict__ krow0, size_t kstride, int H,
-                                              const T *__restrict__ v, float *__restrict__ s_S, int spitch,
-                                              int jcol0, float (&kx)[FW_PF][FW_RJ], float (&vx)[FW_PF]) {
-    const int lane = lane_id();
-    float acc[FW_R][NJ];
+__device__ __forceinline__ float comp(const float4 &x, int c) { return c == 0 ? x.x : c == 1 ? x.y : c == 2 ? x.z : x.w; }
+
+// The keys of one wave as a stream of slices: pass p covers keys j0(p) .. j0(p+1), slice s the columns
+// 256 s + 4 lane .. + 3.  `cur` is the slice about to be consumed; once its values have been used advance()
+// issues the loads of the following slice into the same registers, a whole slice of arithmetic ahead of their
+// use.  Rows past a pass's last key repeat it.
+template <typename T>
+struct KeyStream {
+    const T *kb, *v;
+    int H, lane4, k_lo, npass, NS;
+    int base, extra;                    // pass p has base + (p < extra) keys
+    int p_f, s_f;                       // slice that the next fetch will load
+    float4 cur[FW_NJ], vcur;
+    bool von;
+
+    __device__ __forceinline__ void init(const T *kb_, const T *v_, int H_, int lane, int k_lo_, int nk, int NS_) {
+        kb = kb_;
+        v = v_;
+        H = H_;
+        lane4 = 4 * lane;
+        k_lo = k_lo_;
+        NS = NS_;
+        npass = (nk + FW_NJ - 1) / FW_NJ;
+        const int np = max(npass, 1);
+        base = nk / np;
+        extra = nk - base * np;
+        p_f = 0;
+        s_f = 0;
+    }
+    __device__ __forceinline__ int pass_begin(int p) const { return k_lo + p * base + min(p, extra); }
+
+    // No branches here: past the last slice the loads simply repeat it (a wave without keys reads key 0,
+    // which exists because the block has at least one valid key), so the loads in flight never meet a
+    // control-flow join and stay in flight while the previous slice is being evaluated.
+    __device__ __forceinline__ void fetch() {
+        const int pc = min(p_f, max(npass, 1) - 1);
+        const int j0 = pass_begin(pc), j1 = max(pass_begin(pc + 1), j0 + 1);
+        const int h = s_f * FW_SS + lane4;
+        // columns past H: the load repeats the row's last four values (finite or caught by the limit
+        // check), exp(2q) is 0 there and v reads as 0, so they add nothing
+        const int hc = min(h, H - 4);
 #pragma unroll
-    for (int a = 0; a < FW_R; ++a)
+        for (int c = 0; c < FW_NJ; ++c) {
+            const int j = min(j0 + c, j1 - 1);
+            cur[c] = ld4(kb, (size_t)(unsigned)(j * H + hc));
+        }
+        vcur = ld4(v, (size_t)(unsigned)hc);     // masked by the consumer: von tells whether the columns exist
+        von = h < H;
+        const bool wrap = s_f + 1 == NS;
+        s_f = wrap ? 0 : s_f + 1;
+        p_f = wrap ? min(p_f + 1, npass) : p_f;
+    }
+    __device__ __forceinline__ void start() { fetch(); }
+    __device__ __forceinline__ void advance() { fetch(); }
+};
+
+// One pass of one wave: NJ keys starting at column jcol0 of the score tile, all rows of the block, all slices
+// of h, factor path only.  s_e: LDS rows of exp(2q), pitch Hp.  NI > 0: exactly NI rows are live, known at
+// compile time (no per-row branches, the next row's LDS read is issued a row ahead); NI == 0: the first ni.  Per row the 4 NJ evaluations
+// are issued as three batches (multiply-adds, reciprocals, accumulations) so that no instruction waits for the
+// one before it.  Returns true if a key value was beyond the factor limit, in which case nothing was written
+// and the caller must redo the pass exactly.
+template <typename T, int NG, int NJ, int NI>
+__device__ __forceinline__ bool fw_pass(const float *__restrict__ s_e, int Hp, int ni, KeyStream<T> &ks,
+                                        float *__restrict__ s_S, int spitch, int jcol0) {
+    constexpr int RT = 8 * NG;
+    constexpr bool FULL = NI > 0;
+    constexpr int NR = FULL ? NI : RT;       // rows the unrolled loops visit
+    const int lane = lane_id();
+    float acc[RT][NJ];
+#pragma unroll
+    for (int a = 0; a < RT; ++a)
 #pragma unroll
         for (int c = 0; c < NJ; ++c) acc[a][c] = 0.f;
-    float vsum = 0.f;
-    bool kbig = false;
-    const int nsl = (H + 63) / 64;
+    float vsum = 0.f, kmax = 0.f;
 
-    for (int sl = 0; sl < nsl; ++sl) {
-        const int h0 = sl * 64;
-        const float vh = vx[0];
-        const bool hv = h0 + lane < H;
-        float fk[NJ];
+    for (int s = 0; s < ks.NS; ++s) {
+        float fk[4][NJ], vv[4];
 #pragma unroll
         for (int c = 0; c < NJ; ++c) {
-            const float x = hv ? kx[0][c] : 0.f;
-            kbig |= fabsf(x) > kFactorLimit;
-            fk[c] = fast_exp2(kTwoLog2e * x);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float x = comp(ks.cur[c], q);
+                kmax = fmaxf(kmax, fabsf(x));
+                fk[q][c] = fast_exp2(kTwoLog2e * x);
+            }
         }
-        // rotate the ring (the loop stays rolled, so the code stays small) and refill its last slot
 #pragma unroll
-        for (int u = 0; u + 1 < FW_PF; ++u) {
-#pragma unroll
-            for (int c = 0; c < NJ; ++c) kx[u][c] = kx[u + 1][c];
-            vx[u] = vx[u + 1];
+        for (int q = 0; q < 4; ++q) {
+            vv[q] = ks.von ? comp(ks.vcur, q) : 0.f;
+            vsum += vv[q];
         }
-        if (sl + FW_PF < nsl) {
-            const int hn = h0 + FW_PF * 64 + lane;
-            const int hc = hn < H ? hn : H - 1;
+        ks.advance();
+        const float *e_col = s_e + s * FW_SS + 4 * lane;
+        float4 fq_next = *reinterpret_cast<const float4 *>(e_col);
 #pragma unroll
-            for (int c = 0; c < NJ; ++c) kx[FW_PF - 1][c] = ld(krow0, (size_t)c * kstride + hc);
-            vx[FW_PF - 1] = hn < H ? ld(v, hc) : 0.f;
-        }
-        vsum += vh;
-        float fq[FW_R];
-#pragma unroll
-        for (int a = 0; a < FW_R; ++a) fq[a] = s_e[a * Hp + h0 + lane];
-#pragma unroll
-        for (int a = 0; a < FW_R; ++a) {
+        for (int a = 0; a < NR; ++a) {
             if (FULL || a < ni) {
+                float4 fq;
+                if (FULL) {
+                    fq = fq_next;
+                    if (a + 1 < NR) fq_next = *reinterpret_cast<const float4 *>(e_col + (a + 1) * Hp);
+                } else {
+                    fq = *reinterpret_cast<const float4 *>(e_col + a * Hp);
+                }
+                float t[4][NJ];
 #pragma unroll
-                for (int c = 0; c < NJ; ++c) acc[a][c] = __builtin_fmaf(vh, r_from_factors(fq[a], fk[c]), acc[a][c]);
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int c = 0; c < NJ; ++c) t[q][c] = __builtin_fmaf(comp(fq, q), fk[q][c], 1.0f);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int c = 0; c < NJ; ++c) t[q][c] = fast_rcp(t[q][c]);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int c = 0; c < NJ; ++c) acc[a][c] = __builtin_fmaf(vv[q], t[q][c], acc[a][c]);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
-    if (__any(kbig)) return true;
+    if (__any(kmax > kFactorLimit)) return true;
     // S = sum_h v (1 - 2r): per lane first, then one transposing reduction for the whole tile
-    constexpr int NP = FW_R * NJ;
+    constexpr int NP = RT * NJ;
     constexpr int NPOW = NP <= 8 ? 8 : NP <= 16 ? 16 : NP <= 32 ? 32 : 64;
     float flat[NPOW];
 #pragma unroll
     for (int p = 0; p < NPOW; ++p) {
         const int a = p / NJ, c = p % NJ;
-        flat[p] = p < NP ? __builtin_fmaf(-2.f, acc[a < FW_R ? a : 0][c], vsum) : 0.f;
+        flat[p] = p < NP ? __builtin_fmaf(-2.f, acc[a < RT ? a : 0][c], vsum) : 0.f;
     }
     const float tot = wave_transpose_sum<NPOW>(flat);
     const int p = lane / (64 / NPOW);
     if ((lane % (64 / NPOW)) == 0 && p < NP) {
         const int a = p / NJ, c = p % NJ;
-        if (a < ni) s_S[a * spitch + jcol0 + c * FW_W] = tot;
+        if (a < ni) s_S[a * spitch + jcol0 + c] = tot;
     }
     return false;
 }
@@ -138,56 +205,43 @@ __device__ __forceinline__ bool fw_score_wave(const float *__restrict__ s_e, int
 // The same tile with tanh taken from the exponential of the sum: correct for any finite input.
 // Straightforward loops; only reached for pre-activations beyond the factor limit.
 template <typename T>
-__device__ __noinline__ void fw_score_wave_exact(const T *__restrict__ qrow0, int ni, const T *__restrict__ krow0,
-                                                 size_t kstride, int nj, int H, const T *__restrict__ v,
-                                                 float *__restrict__ s_S, int spitch, int jcol0) {
+__device__ __noinline__ void fw_pass_exact(const T *__restrict__ qrow0, int ni, const T *__restrict__ krow0, int nj,
+                                           int H, const T *__restrict__ v, float *__restrict__ s_S, int spitch,
+                                           int jcol0) {
     const int lane = lane_id();
     for (int a = 0; a < ni; ++a) {
         for (int c = 0; c < nj; ++c) {
             float acc = 0.f;
             for (int h = lane; h < H; h += 64) {
                 const float sq = kTwoLog2e * ld(qrow0, (size_t)a * H + h);
-                const float sk = kTwoLog2e * ld(krow0, (size_t)c * kstride + h);
+                const float sk = kTwoLog2e * ld(krow0, (size_t)c * H + h);
                 const float vh = ld(v, h);
                 acc += vh * __builtin_fmaf(-2.f, r_from_sum(sq, sk), 1.f);
             }
             acc = wave_sum(acc);
-            if (lane == 0) s_S[a * spitch + jcol0 + c * FW_W] = acc;
+            if (lane == 0) s_S[a * spitch + jcol0 + c] = acc;
         }
     }
 }
 
-// Which (sample, row tile) this block works on; see "Placement" at the top.  s_i: scratch of
-// 2*B + 2 ints in LDS.  Returns false if the block has nothing to do.
-__device__ __forceinline__ bool fw_pick_item(const int *__restrict__ key_len, int B, int Tq, int Tk, int tiles,
-                                             int ranked, int *s_i, int &b, int &tile) {
+// Which (sample, row tile) this block works on and the sample's valid keys; see "Placement" at the top.
+// Ranked mode: wave 0 finds the sample that holds a given rank by radix selection over composite keys
+// (valid keys, then index) held two per lane, and hands the answer to the other waves through s_pick.
+// Returns false if the block has nothing to do (uniformly for the whole block).
+__device__ __forceinline__ bool fw_pick_item(const int *__restrict__ key_len, int B, int Tk, int tiles, int ranked,
+                                             int *s_pick, int &b, int &tile, int &L) {
     const int xcd = blockIdx.x % FW_XCD, li = blockIdx.x / FW_XCD;
     if (!ranked) {                         // samples x, x+8, ... on XCD x, in index order
         b = xcd + FW_XCD * (li / tiles);
         tile = li % tiles;
-        return b < B;
+        if (b >= B) return false;
+        L = clamp_len(key_len[b], Tk);
+        return true;
     }
-    int *s_len = s_i, *s_xb = s_i + B, *s_cnt = s_i + 2 * B;
-    for (int o = threadIdx.x; o < B; o += FW_THREADS) s_len[o] = clamp_len(key_len[o], Tk);
-    if (threadIdx.x == 0) *s_cnt = 0;
-    __syncthreads();
-    for (int cand = threadIdx.x; cand < B; cand += FW_THREADS) {
-        const int lc = s_len[cand];
-        int r = 0;                         // rank by valid keys, most first, ties by index
-        for (int o = 0; o < B; ++o) {
-            const int lo = s_len[o];
-            r += (lo > lc) || (lo == lc && o < cand);
-        }
-        const int q = r % (2 * FW_XCD);
-        const int x = q < FW_XCD ? q : 2 * FW_XCD - 1 - q;     // snake over the XCDs
-        if (x == xcd) {
-            s_xb[(r / (2 * FW_XCD)) * 2 + (q >= FW_XCD ? 1 : 0)] = cand;   // position inside the XCD, heaviest first
-            atomicAdd(s_cnt, 1);
-        }
-    }
-    __syncthreads();
-    const int M = *s_cnt;                  // samples of this XCD
-    const int n = M * tiles;               // its tiles
+    // samples of this XCD: ranks 16 g + xcd and 16 g + 15 - xcd (snake over the XCDs), heaviest first
+    const int rem = B % (2 * FW_XCD);
+    const int M = 2 * (B / (2 * FW_XCD)) + (xcd < rem ? 1 : 0) + (2 * FW_XCD - 1 - xcd < rem ? 1 : 0);
+    const int n = M * tiles;               // tiles of this XCD
     if (li >= n) return false;
     // position in the launch order -> position in "heaviest first" order
     int rho = li;
@@ -197,68 +251,66 @@ __device__ __forceinline__ bool fw_pick_item(const int *__restrict__ key_len, in
         else if (li >= FW_CU_PER_XCD - singles) rho = li - (FW_CU_PER_XCD - singles);
         else rho = singles + li;
     }
-    // heaviest-first list: sample by sample (the tiles of a sample weigh the same)
-    const int m = rho / tiles;
+    const int m = rho / tiles;             // the tiles of a sample weigh the same
     tile = rho % tiles;
-    b = s_xb[m];
+    if (wave_id() == 0) {
+        const int lane = lane_id();
+        const int c0 = lane, c1 = lane + 64;
+        // larger key = more valid keys, ties to the lower index; bits: length above 7 bits of (127 - index)
+        const unsigned key0 = c0 < B ? ((unsigned)clamp_len(key_len[c0], Tk) << 7) | (unsigned)(127 - c0) : 0u;
+        const unsigned key1 = c1 < B ? ((unsigned)clamp_len(key_len[c1], Tk) << 7) | (unsigned)(127 - c1) : 0u;
+        unsigned long long act0 = __ballot(c0 < B), act1 = __ballot(c1 < B);
+        int r = (m / 2) * (2 * FW_XCD) + ((m & 1) ? 2 * FW_XCD - 1 - xcd : xcd);   // keys larger than the wanted one
+        const int top = 7 + 32 - __builtin_clz((unsigned)Tk);                        // bits in use
+        for (int bit = top - 1; bit >= 0; --bit) {
+            const unsigned long long m0 = __ballot((key0 >> bit) & 1u) & act0;
+            const unsigned long long m1 = __ballot((key1 >> bit) & 1u) & act1;
+            const int cnt = __popcll(m0) + __popcll(m1);
+            if (cnt > r) {
+                act0 = m0;
+                act1 = m1;
+            } else {
+                r -= cnt;
+                act0 &= ~m0;
+                act1 &= ~m1;
+            }
+        }
+        // exactly one candidate is left
+        const bool mine = act0 ? ((act0 >> lane) & 1ull) != 0 : ((act1 >> lane) & 1ull) != 0;
+        if (mine) {
+            s_pick[0] = act0 ? c0 : c1;
+            s_pick[1] = (int)((act0 ? key0 : key1) >> 7);
+        }
+    }
+    __syncthreads();
+    b = s_pick[0];
+    L = s_pick[1];
     return true;
 }
 
-template <typename T>
-__global__ __launch_bounds__(FW_THREADS, 4) void k_fwd_fused(
+template <typename T, int NG>
+__global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
     const T *__restrict__ Qp, const T *__restrict__ Kp, const T *__restrict__ V, const T *__restrict__ v,
     const int *__restrict__ key_len, float *__restrict__ C, float *__restrict__ P,
     int B, int Tq, int Tk, int H, int Dv, int tiles, int Hp, int spitch, int ranked) {
-    extern __shared__ float smem[];
-    float *s_e = smem;                       // [FW_R][Hp]  exp(2q)
-    float *s_S = s_e + FW_R * Hp;            // [FW_R][spitch]  scores, then probabilities
+    constexpr int RT = 8 * NG;
+    extern __shared__ __align__(16) float smem[];
+    float *s_e = smem;                       // [RT][Hp]  exp(2q)
+    float *s_S = s_e + RT * Hp;              // [RT][spitch]  scores, then probabilities
 
     const int lane = lane_id(), w = wave_id();
     FW_STAMP(0);
 
-    int b, tile;
-    if (!fw_pick_item(key_len, B, Tq, Tk, tiles, ranked, reinterpret_cast<int *>(smem), b, tile)) return;
-    if (ranked) __syncthreads();             // the scratch is about to be overwritten by the staging
+    __shared__ int s_pick[2];
+    int b, tile, L;
+    if (!fw_pick_item(key_len, B, Tk, tiles, ranked, s_pick, b, tile, L)) return;
+    b = __builtin_amdgcn_readfirstlane(b);
+    tile = __builtin_amdgcn_readfirstlane(tile);
+    L = __builtin_amdgcn_readfirstlane(L);
     const int r0 = (int)(((long long)Tq * tile) / tiles);      // rows are split evenly over the tiles
-    const int ni = (int)(((long long)Tq * (tile + 1)) / tiles) - r0;   // 1..FW_R
+    const int ni = (int)(((long long)Tq * (tile + 1)) / tiles) - r0;   // 1..RT
     FW_STAMP(1);
 
-    // ---- loads first: the query rows ...
-    const T *qb = Qp + ((size_t)b * Tq + r0) * H;
-    constexpr int QMAX = 2;                                   // column passes per batch (H <= 1024 in one batch)
-    float qx[QMAX][FW_R];
-    auto q_fetch = [&](int col0) {
-#pragma unroll
-        for (int m = 0; m < QMAX; ++m) {
-            const int h = col0 + m * FW_THREADS + threadIdx.x;
-#pragma unroll
-            for (int a = 0; a < FW_R; ++a) qx[m][a] = (a < ni && h < H) ? ld(qb, (size_t)a * H + h) : 0.f;
-        }
-    };
-    q_fetch(0);
-
-    // ... and the first FW_PF slices of this wave's keys of chunk 0.  Wave w owns keys
-    // 32 ch + 8 c + w (c < FW_RJ) of chunk ch; rows past Tk are clamped and never used.
-    const T *kb = Kp + (size_t)b * Tk * H;
-    const int nsl = (H + 63) / 64;
-    float kx[FW_PF][FW_RJ], vx[FW_PF];
-    auto k_prefetch = [&](int ch) {
-#pragma unroll
-        for (int u = 0; u < FW_PF; ++u) {
-            const int hn = u * 64 + lane;
-            const int hc = hn < H ? hn : H - 1;
-            const bool on = u < nsl;
-#pragma unroll
-            for (int c = 0; c < FW_RJ; ++c) {
-                const int j = min(ch * FW_CHUNK + c * FW_W + w, Tk - 1);
-                kx[u][c] = on ? ld(kb, (size_t)j * H + hc) : 0.f;
-            }
-            vx[u] = (on && hn < H) ? ld(v, hc) : 0.f;
-        }
-    };
-    k_prefetch(0);
-
-    const int L = clamp_len(key_len[b], Tk);
     float *Pb = P + ((size_t)b * Tq + r0) * Tk;
     float *Cb = C + ((size_t)b * Tq + r0) * Dv;
     if (L == 0) {                                             // no valid key: zeros
@@ -270,67 +322,83 @@ __global__ __launch_bounds__(FW_THREADS, 4) void k_fwd_fused(
     if (threadIdx.x == 0 && blockIdx.x < 16384) g_stamps[blockIdx.x * 8 + 2] = ((long long)b << 40) | ((long long)tile << 24) | ((long long)ni << 16) | L;
 #endif
 
-    // ---- A: exp(2q) to LDS (rows past ni and columns past H as zeros)
+    // ---- loads first: this wave's first key slice ...
+    const T *qb = Qp + ((size_t)b * Tq + r0) * H;
+    const T *kb = Kp + (size_t)b * Tk * H;
+    KeyStream<T> ks;
+    {
+        const int k_lo = (L * w) / FW_W;
+        ks.init(kb, v, H, lane, k_lo, (L * (w + 1)) / FW_W - k_lo, Hp / FW_SS);
+    }
+    ks.start();
+
+    // ---- A: ... then exp(2q) to LDS (rows past ni and columns past H as zeros), four loads per thread in flight
     bool big = false;
-    for (int col0 = 0; col0 < Hp; col0 += QMAX * FW_THREADS) {
-        if (col0 > 0) q_fetch(col0);
+    const int q4 = Hp / 4;                                    // 16-byte columns per row
+    for (int e0 = threadIdx.x; e0 < RT * q4; e0 += 4 * FW_THREADS) {
+        float4 x[4];
 #pragma unroll
-        for (int m = 0; m < QMAX; ++m) {
-            const int h = col0 + m * FW_THREADS + threadIdx.x;
-            if (h < Hp) {
+        for (int u = 0; u < 4; ++u) {
+            const int e = e0 + u * FW_THREADS;
+            const int a = e / q4, h = 4 * (e % q4);
+            x[u] = (e < RT * q4 && a < ni && h < H) ? ld4(qb, (size_t)a * H + h) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
 #pragma unroll
-                for (int a = 0; a < FW_R; ++a) {
-                    big |= fabsf(qx[m][a]) > kFactorLimit;
-                    s_e[a * Hp + h] = (a < ni && h < H) ? fast_exp2(kTwoLog2e * qx[m][a]) : 0.f;
-                }
+        for (int u = 0; u < 4; ++u) {
+            const int e = e0 + u * FW_THREADS;
+            if (e < RT * q4) {
+                const int a = e / q4, h = 4 * (e % q4);
+                const bool on = a < ni && h < H;
+                big |= fmaxf(fmaxf(fabsf(x[u].x), fabsf(x[u].y)), fmaxf(fabsf(x[u].z), fabsf(x[u].w))) > kFactorLimit;
+                float4 y;
+                y.x = on ? fast_exp2(kTwoLog2e * x[u].x) : 0.f;
+                y.y = on ? fast_exp2(kTwoLog2e * x[u].y) : 0.f;
+                y.z = on ? fast_exp2(kTwoLog2e * x[u].z) : 0.f;
+                y.w = on ? fast_exp2(kTwoLog2e * x[u].w) : 0.f;
+                *reinterpret_cast<float4 *>(s_e + a * Hp + h) = y;
             }
         }
     }
     const bool qbig = __syncthreads_or(big) != 0;
     FW_STAMP(3);
 
-    // ---- B: scores, keys in chunks of FW_CHUNK
-    const int n_chunk = (L + FW_CHUNK - 1) / FW_CHUNK;
-    for (int ch = 0; ch < n_chunk; ++ch) {
-        if (ch > 0) k_prefetch(ch);
-        const int j0 = ch * FW_CHUNK + w;                      // first key of this wave in the chunk
-        const int nj = j0 < L ? min(FW_RJ, (L - 1 - j0) / FW_W + 1) : 0;
-        const T *krow0 = kb + (size_t)j0 * H;
-        const size_t kstride = (size_t)FW_W * H;
-        bool redo = qbig && nj > 0;
-        if (!qbig) {
-#define FW_CASE(N)                                                                                         \
-    case N:                                                                                                \
-        redo = (ni == FW_R) ? fw_score_wave<T, N, true>(s_e, Hp, ni, krow0, kstride, H, v, s_S, spitch, j0, kx, vx) \
-                            : fw_score_wave<T, N, false>(s_e, Hp, ni, krow0, kstride, H, v, s_S, spitch, j0, kx, vx); \
+    // ---- B: scores, this wave's keys in passes of up to FW_NJ
+    for (int p = 0; p < ks.npass; ++p) {
+        const int j0 = ks.pass_begin(p);
+        const int nj = ks.pass_begin(p + 1) - j0;              // 1..FW_NJ
+        bool redo = true;
+#define FW_CASE(N)                                                                            \
+    case N:                                                                                   \
+        redo = (ni == RT)       ? fw_pass<T, NG, N, RT>(s_e, Hp, ni, ks, s_S, spitch, j0)     \
+               : (ni == RT - 1) ? fw_pass<T, NG, N, RT - 1>(s_e, Hp, ni, ks, s_S, spitch, j0) \
+                                : fw_pass<T, NG, N, 0>(s_e, Hp, ni, ks, s_S, spitch, j0);     \
         break;
-            switch (nj) {
-                FW_CASE(1) FW_CASE(2) FW_CASE(3) FW_CASE(4)
-                default: break;
-            }
-#undef FW_CASE
+        switch (nj) {
+            FW_CASE(1) FW_CASE(2) FW_CASE(3) FW_CASE(4)
+            default: break;
         }
-        if (redo) fw_score_wave_exact<T>(qb, ni, krow0, kstride, nj, H, v, s_S, spitch, j0);
+#undef FW_CASE
+        if (redo || qbig) fw_pass_exact<T>(qb, ni, kb + (size_t)j0 * H, nj, H, v, s_S, spitch, j0);
     }
 
     // first batch of value rows for the context phase leaves before the softmax
     const T *vb = V + (size_t)b * Tk * Dv;
     const int Lp = (L + 3) & ~3;
     const int n_grp = (Dv + 63) / 64;
-    float vv[FW_KB];
-    auto v_fetch = [&](int g, int kb0) {
-        const int n = g * 64 + lane;
-        const int nc = n < Dv ? n : Dv - 1;
+    float vcur[FW_KB], vnxt[FW_KB];
+    // rows kb0 .. kb0 + FW_KB - 1 of column group g; keys past L carry P = 0, the last valid row stands in for
+    // them; no branches, so that the loads stay in flight across the arithmetic of the batch before
+    auto v_fetch = [&](float (&dst)[FW_KB], int g, int kb0) {
+        const int n = min(g * 64 + lane, Dv - 1);
 #pragma unroll
-        for (int kk = 0; kk < FW_KB; ++kk)   // keys past L carry P = 0; the last valid row stands in for them
-            if (kb0 + kk < Lp) vv[kk] = ld(vb, (size_t)min(kb0 + kk, L - 1) * Dv + nc);
+        for (int kk = 0; kk < FW_KB; ++kk) dst[kk] = ld(vb, (size_t)(unsigned)(min(kb0 + kk, L - 1) * Dv + n));
     };
-    if (w < n_grp) v_fetch(w, 0);
+    v_fetch(vcur, min(w, n_grp - 1), 0);
     __syncthreads();
     FW_STAMP(4);
 
-    // ---- C: softmax, wave r <-> row r; probabilities replace the scores in LDS
-    for (int a = w; a < FW_R; a += FW_W) {
+    // ---- C: softmax, waves take rows in turn; probabilities replace the scores in LDS
+    for (int a = w; a < RT; a += FW_W) {
         float *srow = s_S + a * spitch;
         if (a < ni) {
             float m = -INFINITY;
@@ -358,33 +426,51 @@ __global__ __launch_bounds__(FW_THREADS, 4) void k_fwd_fused(
 
     // ---- D: context rows = P V.  A wave takes 64 columns at a time; lane l owns column n0 + l.
     // One 4x4x1 MFMA multiplies 4 rows of P (replicated over the 16 lane groups) with one V value per lane.
+    // The batches of value rows of all of a wave's column groups form one sequence; the loads of the next
+    // batch are issued before the current one is multiplied.
     const int lr = lane & 3;
-    for (int g = w; g < n_grp; g += FW_W) {
-        const int n = g * 64 + lane;
-        f32x4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = a0;              // rows 0-3 / 4-7
-        for (int kb0 = 0; kb0 < Lp; kb0 += FW_KB) {
-            if (g != w || kb0 > 0) v_fetch(g, kb0);
+    constexpr int NR4 = RT / 4;
+    f32x4 acc[NR4];
 #pragma unroll
-            for (int k4 = 0; k4 < FW_KB; k4 += 4) {
-                if (kb0 + k4 < Lp) {
-                    const float4 pa = *reinterpret_cast<const float4 *>(s_S + lr * spitch + kb0 + k4);
-                    const float4 pb = *reinterpret_cast<const float4 *>(s_S + (4 + lr) * spitch + kb0 + k4);
-                    const float pav[4] = {pa.x, pa.y, pa.z, pa.w}, pbv[4] = {pb.x, pb.y, pb.z, pb.w};
+    for (int t = 0; t < NR4; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    int g = w, kb0 = 0;
+    while (g < n_grp) {
+        int g2 = g, kb2 = kb0 + FW_KB;
+        if (kb2 >= Lp) {
+            g2 = g + FW_W;
+            kb2 = 0;
+        }
+        v_fetch(vnxt, min(g2, n_grp - 1), kb2);
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        a0 = __builtin_amdgcn_mfma_f32_4x4x1f32(pav[q], vv[k4 + q], a0, 0, 0, 0);
-                        a1 = __builtin_amdgcn_mfma_f32_4x4x1f32(pbv[q], vv[k4 + q], a1, 0, 0, 0);
-                    }
-                }
+        for (int k4 = 0; k4 < FW_KB; k4 += 4) {
+            if (kb0 + k4 < Lp) {
+                float4 pr[NR4];
+#pragma unroll
+                for (int t = 0; t < NR4; ++t)
+                    pr[t] = *reinterpret_cast<const float4 *>(s_S + (4 * t + lr) * spitch + kb0 + k4);
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int t = 0; t < NR4; ++t)
+                        acc[t] = __builtin_amdgcn_mfma_f32_4x4x1f32(comp(pr[t], q), vcur[k4 + q], acc[t], 0, 0, 0);
             }
         }
-        if (n < Dv) {
+        if (kb2 == 0) {                                        // last batch of column group g
+            const int n = g * 64 + lane;
+            if (n < Dv) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                if (r < ni) Cb[(size_t)r * Dv + n] = a0[r];
-                if (4 + r < ni) Cb[(size_t)(4 + r) * Dv + n] = a1[r];
+                for (int t = 0; t < NR4; ++t)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (4 * t + r < ni) Cb[(size_t)(4 * t + r) * Dv + n] = acc[t][r];
             }
+#pragma unroll
+            for (int t = 0; t < NR4; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
         }
+#pragma unroll
+        for (int kk = 0; kk < FW_KB; ++kk) vcur[kk] = vnxt[kk];
+        g = g2;
+        kb0 = kb2;
     }
     FW_STAMP(6);
 #ifdef ECHO_TIMING
@@ -403,40 +489,48 @@ extern "C" int echo_debug_stamps(long long *host, int n) {
 }
 #endif
 
-size_t fwd_fused_lds_bytes(const AttnShape &s) {
-    const int Hp = (s.H + 63) / 64 * 64;
+// Rows per block: 8.  (16 rows halve the exponentials of K per score, but need twice the accumulators; with
+// two waves per SIMD instead of four that measured 20-25 % slower on the large workloads.)
+
+static size_t fwd_lds_bytes(const AttnShape &s, int ng) {
+    const int Hp = (s.H + FW_SS - 1) / FW_SS * FW_SS;
     const int spitch = ((s.Tk + 3) & ~3) + 4;
-    const size_t stage = (size_t)(FW_R * Hp + FW_R * spitch) * sizeof(float);
-    const size_t rank_scratch = (size_t)(2 * s.B + 2) * sizeof(int);
-    return stage > rank_scratch ? stage : rank_scratch;
+    return (size_t)(8 * ng) * (Hp + spitch) * sizeof(float);
 }
 
-template <typename T>
+bool fwd_fused_supported(const AttnShape &s) {
+    return s.H % 4 == 0 && fwd_lds_bytes(s, 1) <= 150 * 1024;
+}
+
+template <typename T, int NG>
 static hipError_t launch_fwd_fused_t(const AttnShape &s, const void *Qp, const void *Kp, const void *V, const void *v,
                                      const int *key_len, float *C, float *P, hipStream_t st) {
-    const int Hp = (s.H + 63) / 64 * 64;
+    constexpr int RT = 8 * NG;
+    const int Hp = (s.H + FW_SS - 1) / FW_SS * FW_SS;
     const int spitch = ((s.Tk + 3) & ~3) + 4;
-    const size_t lds = fwd_fused_lds_bytes(s);
+    const size_t lds = fwd_lds_bytes(s, NG);
     static size_t attr_bytes = 48 * 1024;   // dynamic LDS limit already granted to this instantiation
     if (lds > attr_bytes) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_fwd_fused<T>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)lds);
+        hipError_t e = hipFuncSetAttribute((const void *)k_fwd_fused<T, NG>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_bytes = lds;
     }
-    const int tiles = (s.Tq + FW_R - 1) / FW_R;
+    const int tiles = (s.Tq + RT - 1) / RT;
     const int samples_per_xcd = (s.B + FW_XCD - 1) / FW_XCD;
-    const int grid = FW_XCD * samples_per_xcd * tiles;
+    const long long grid = (long long)FW_XCD * samples_per_xcd * tiles;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     const int ranked = s.B <= FW_MAX_RANKED_B ? 1 : 0;
-    k_fwd_fused<T><<<grid, FW_THREADS, lds, st>>>((const T *)Qp, (const T *)Kp, (const T *)V, (const T *)v, key_len, C,
-                                                  P, s.B, s.Tq, s.Tk, s.H, s.Dv, tiles, Hp, spitch, ranked);
+    k_fwd_fused<T, NG><<<(unsigned)grid, FW_THREADS, lds, st>>>((const T *)Qp, (const T *)Kp, (const T *)V,
+                                                               (const T *)v, key_len, C, P, s.B, s.Tq, s.Tk, s.H, s.Dv,
+                                                               tiles, Hp, spitch, ranked);
     return hipGetLastError();
 }
 
 hipError_t launch_fwd_fused(const AttnShape &s, const void *Qp, const void *Kp, const void *V, const void *v,
                             const int *key_len, float *C, float *P, hipStream_t st) {
-    return s.bf16 ? launch_fwd_fused_t<bf16_t>(s, Qp, Kp, V, v, key_len, C, P, st)
-                  : launch_fwd_fused_t<float>(s, Qp, Kp, V, v, key_len, C, P, st);
+    return s.bf16 ? launch_fwd_fused_t<bf16_t, 1>(s, Qp, Kp, V, v, key_len, C, P, st)
+                  : launch_fwd_fused_t<float, 1>(s, Qp, Kp, V, v, key_len, C, P, st);
 }
 
 }  // namespace echo
