@@ -49,7 +49,7 @@ __device__ __forceinline__ void pv_block(const float *__restrict__ P, const TB *
 
     if (m0 < Mvalid) {
         const int m = m0 + lm;
-        constexpr int U = 8;                      // k-steps whose loads are in flight together
+        constexpr int U = TRANS_A ? 16 : 8;       // k-steps whose loads are in flight together
         for (int kb0 = 0; kb0 < K; kb0 += 4 * U) {
             float a[U];
             float4 bv[U];
@@ -178,6 +178,137 @@ __device__ __forceinline__ void dscore_block(const float *__restrict__ dC, const
     }
 }
 
+#ifdef ECHO_TIMING   // development aid: per-block time stamps (100 MHz counter), read back with echo_debug_stamps_pre
+__device__ long long g_pre_stamps[16384 * 4];
+#define PRE_STAMP(k)                                                                                      \
+    do {                                                                                                  \
+        if (threadIdx.x == 0 && blockIdx.x < 16384) g_pre_stamps[blockIdx.x * 4 + (k)] = wall_clock64();  \
+    } while (0)
+extern "C" int echo_debug_stamps_pre(long long *host, int n) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_pre_stamps), (size_t)n * sizeof(long long));
+}
+#else
+#define PRE_STAMP(k)
+#endif
+
+// The same for short key axes (Tk <= kDsplitMaxTk): latency, not arithmetic, decides here, so the four waves
+// split d instead of the key tiles.  Wave w owns the columns d of every fourth 128-wide chunk, keeps its slice
+// of the 16 dC rows in registers across the key tiles when Dv <= 512, has the V slice of the next key tile in
+// flight while the current one is multiplied, and leaves a partial dP tile in its own LDS plane; the planes
+// are added in wave order by the finishing phase, whose P rows were requested at the very start.
+// Rows and keys past the end are clamped for loading; what they produce is never read.
+constexpr int kDsplitMaxTk = 128;
+template <typename TV>
+__device__ __forceinline__ void dscore_block_dsplit(const float *__restrict__ dC, const TV *__restrict__ V,
+                                                    const float *__restrict__ P, const int *__restrict__ key_len,
+                                                    float *__restrict__ dS, float *__restrict__ ds_rowsum,
+                                                    float *__restrict__ s_dp, int b, int i0, int Tq, int Tk,
+                                                    int Dv, int pitch) {
+    const int lane = lane_id(), w = wave_id();
+    const int lm = lane & 15, lk = lane >> 4;
+    const int pitch16 = (Tk + 15) / 16 * 16 + 4;
+    const int plane = 16 * pitch16;
+    // P of the rows this wave finishes (rows w, w+4, w+8, w+12 of the tile), two keys per lane
+    float pr[4][2];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int i = min(i0 + w + 4 * t, Tq - 1);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) pr[t][u] = P[((size_t)b * Tq + i) * Tk + min(lane + 64 * u, Tk - 1)];
+    }
+    const int L = clamp_len(key_len[b], Tk);
+    const float *dCrow = dC + ((size_t)b * Tq + min(i0 + lm, Tq - 1)) * Dv;
+    const TV *Vb = V + (size_t)b * Tk * Dv;
+    constexpr int U = 8;                          // 16-wide slices of d per wave and round
+    const int rounds = (Dv + 64 * U - 1) / (64 * U);
+    const int n_jt = (L + 15) / 16;
+    const int items = n_jt * rounds;
+    float4 a[U], bcur[U], bnxt[U];
+    auto load_a = [&](int r) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int d = (4 * r + w) * 16 * U + 16 * u + 4 * lk;
+            const float4 x = ld4(dCrow, (size_t)min(d, Dv - 4));
+            a[u] = d < Dv ? x : make_float4(0.f, 0.f, 0.f, 0.f);     // columns past Dv add nothing
+        }
+    };
+    auto load_b = [&](float4 (&dst)[U], int it) {
+        const int jt = it / rounds, r = it % rounds;
+        const TV *row = Vb + (size_t)min(jt * 16 + lm, Tk - 1) * Dv;
+#pragma unroll
+        for (int u = 0; u < U; ++u) dst[u] = ld4(row, (size_t)min((4 * r + w) * 16 * U + 16 * u + 4 * lk, Dv - 4));
+    };
+    if (items > 0) {
+        load_b(bcur, 0);
+        load_a(0);
+    }
+    f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int it = 0; it < items; ++it) {
+        const int jt = it / rounds, r = it % rounds;
+        load_b(bnxt, min(it + 1, items - 1));
+        if (rounds > 1 && it > 0) load_a(r);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            acc = mfma16(a[u].x, bcur[u].x, acc);
+            acc = mfma16(a[u].y, bcur[u].y, acc);
+            acc = mfma16(a[u].z, bcur[u].z, acc);
+            acc = mfma16(a[u].w, bcur[u].w, acc);
+        }
+        if (r == rounds - 1) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) s_dp[w * plane + (4 * lk + q) * pitch16 + jt * 16 + lm] = acc[q];
+            acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) bcur[u] = bnxt[u];
+    }
+    PRE_STAMP(2);
+    __syncthreads();
+    PRE_STAMP(3);
+
+    // the four rows together: r = sum_j P dP and sum_j dS by transposing reductions (sum of row t ends up in
+    // lanes 16 t .. 16 t + 15), so the exchanges of the rows overlap instead of queueing behind each other
+    float dp[4][2], rsum[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int rr = w + 4 * t;
+        rsum[t] = 0.f;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int j = lane + 64 * u;
+            const float *q = s_dp + rr * pitch16 + min(j, pitch16 - 1);
+            const float x = ((q[0] + q[plane]) + q[2 * plane]) + q[3 * plane];
+            dp[t][u] = j < L ? x : 0.f;
+            rsum[t] = __builtin_fmaf(j < L ? pr[t][u] : 0.f, dp[t][u], rsum[t]);
+        }
+    }
+    const float r4 = wave_transpose_sum<4>(rsum);
+    float tsum[4], dsv[4][2];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const float r = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(r4), 16 * t));
+        tsum[t] = 0.f;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int j = lane + 64 * u;
+            dsv[t][u] = j < L ? pr[t][u] * (dp[t][u] - r) : 0.f;
+            tsum[t] += dsv[t][u];
+        }
+    }
+    const float t4 = wave_transpose_sum<4>(tsum);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int i = i0 + w + 4 * t;
+        if (i < Tq) {
+            float *ds = dS + ((size_t)b * Tq + i) * pitch;
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+                if (lane + 64 * u < pitch) ds[lane + 64 * u] = dsv[t][u];
+            if (lane == 16 * t) ds_rowsum[(size_t)b * Tq + i] = t4;
+        }
+    }
+}
+
 // For the recompute kernel: order[r] = b | L_b << 16 for the sample b with the
 // r-th most valid keys (ties by index), or r-th in index order when `sorted` is 0.  With `fold` the second
 // half runs lightest first: when the whole recompute grid is resident at once,
@@ -207,30 +338,38 @@ __device__ __forceinline__ void rank_block(const int *__restrict__ key_len, int 
 // block 0 ranks the samples, the next nS blocks produce dS (B1 + B2), the
 // rest produce dV (B1).  The three kinds of block do not depend on each other.
 template <typename TV>
-__global__ __launch_bounds__(256) void k_bwd_pre(const float *__restrict__ dC, const TV *__restrict__ V,
+__global__ __launch_bounds__(256, 3) void k_bwd_pre(const float *__restrict__ dC, const TV *__restrict__ V,
                                                  const float *__restrict__ P, const int *__restrict__ key_len,
                                                  float *__restrict__ dS, float *__restrict__ ds_rowsum,
                                                  int *__restrict__ order, float *__restrict__ dV, int B, int sorted,
                                                  int fold,
                                                  int Tq, int Tk, int Dv, int pitch, int s_tiles, int v_xt, int v_yt) {
-    extern __shared__ float s_dp[];           // [16][pitch16]
+    extern __shared__ float s_dp[];           // [16][pitch16], four such planes when Tk <= kDsplitMaxTk
     __shared__ int s_len[kMaxSortedB];
     int bid = blockIdx.x;
+    PRE_STAMP(0);
     if (bid == 0) {
         rank_block(key_len, order, s_len, B, Tk, sorted, fold);
+        PRE_STAMP(1);
         return;
     }
     bid -= 1;
     const int nS = s_tiles * B;
     if (bid < nS) {
-        dscore_block<TV>(dC, V, P, key_len, dS, ds_rowsum, s_dp, bid / s_tiles, (bid % s_tiles) * 16, Tq, Tk, Dv,
-                         pitch);
+        if (Tk <= kDsplitMaxTk)
+            dscore_block_dsplit<TV>(dC, V, P, key_len, dS, ds_rowsum, s_dp, bid / s_tiles, (bid % s_tiles) * 16, Tq,
+                                    Tk, Dv, pitch);
+        else
+            dscore_block<TV>(dC, V, P, key_len, dS, ds_rowsum, s_dp, bid / s_tiles, (bid % s_tiles) * 16, Tq, Tk, Dv,
+                             pitch);
+        PRE_STAMP(1);
         return;
     }
     bid -= nS;
     const int per_b = v_xt * v_yt;
     const int b = bid / per_b, rem = bid % per_b;
     pv_block<float, true>(P, dC, key_len, dV, Tq, Tk, Dv, b, rem / v_xt, rem % v_xt);
+    PRE_STAMP(1);
 }
 
 hipError_t launch_bwd_pre(const AttnShape &s, const float *dC, const void *V, const float *P, const int *key_len,
@@ -243,7 +382,7 @@ hipError_t launch_bwd_pre(const AttnShape &s, const float *dC, const void *V, co
     const long long blocks = 1 + (long long)s.B * s_tiles + (long long)s.B * v_xt * v_yt;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     const int pitch16 = (s.Tk + 15) / 16 * 16 + 4;
-    const size_t lds = (size_t)16 * pitch16 * sizeof(float);
+    const size_t lds = (size_t)(s.Tk <= kDsplitMaxTk ? 4 : 1) * 16 * pitch16 * sizeof(float);
     if (lds > 48 * 1024) {   // beyond the default dynamic LDS limit: raise it (up to 160 KB per block on gfx950)
         hipError_t e = s.bf16 ? hipFuncSetAttribute((const void *)k_bwd_pre<bf16_t>,
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
