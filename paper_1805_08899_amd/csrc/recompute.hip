@@ -57,21 +57,41 @@ __device__ __forceinline__ void rc_tile(const float (&fq)[RC_RI], const float (&
                                         const float *__restrict__ ds_tile, int pitch,
                                         const float *__restrict__ t_tile, size_t t_row, size_t t_key,
                                         const int (&kcol)[RC_RJ],
-                                        float (&accQ)[RC_RI], float (&accK)[RC_RJ], float &accV) {
+                                        float (&accQ)[RC_RI], float (&accK)[RC_RJ], float (&accV)[4]) {
+    // Row by row; the eight evaluations of a row are issued as batches (multiply-adds, reciprocals, ...) so
+    // that no instruction waits for the one before it.
 #pragma unroll
     for (int a = 0; a < NI; ++a) {
+        const float4 d0 = *reinterpret_cast<const float4 *>(ds_tile + a * pitch);
+        const float4 d1 = *reinterpret_cast<const float4 *>(ds_tile + a * pitch + 4);
+        const float d[RC_RJ] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+        float r[RC_RJ], u[RC_RJ];
+        if (MODE == RC_STASH) {
 #pragma unroll
-        for (int c = 0; c < RC_RJ; ++c) {
-            const float d = ds_tile[a * pitch + c];
-            float r;
-            if (MODE == RC_FACTOR) r = r_from_factors(fq[a], fk[c]);
-            else if (MODE == RC_EXACT) r = r_from_sum(fq[a], fk[c]);
-            else r = __builtin_fmaf(-0.5f, t_tile[a * t_row + kcol[c] * t_key], 0.5f);
-            const float u = __builtin_fmaf(-r, r, r);          // r (1 - r) = (1 - t^2) / 4
-            accQ[a] = __builtin_fmaf(d, u, accQ[a]);
-            accK[c] = __builtin_fmaf(d, u, accK[c]);
-            accV = __builtin_fmaf(d, r, accV);
+            for (int c = 0; c < RC_RJ; ++c) r[c] = __builtin_fmaf(-0.5f, t_tile[a * t_row + kcol[c] * t_key], 0.5f);
+        } else {
+#pragma unroll
+            for (int c = 0; c < RC_RJ; ++c)
+                r[c] = MODE == RC_FACTOR ? __builtin_fmaf(fq[a], fk[c], 1.0f) : fast_exp2(fq[a] + fk[c]) + 1.0f;
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int c = 0; c < RC_RJ; ++c) r[c] = fast_rcp(r[c]);
+            __builtin_amdgcn_sched_barrier(0);
         }
+#pragma unroll
+        for (int c = 0; c < RC_RJ; ++c) u[c] = __builtin_fmaf(-r[c], r[c], r[c]);      // r (1 - r) = (1 - t^2) / 4
+        float q0 = 0.f, q1 = 0.f;
+#pragma unroll
+        for (int c = 0; c < RC_RJ; c += 2) {
+            accK[c] = __builtin_fmaf(d[c], u[c], accK[c]);
+            q0 = __builtin_fmaf(d[c], u[c], q0);
+            accV[c & 3] = __builtin_fmaf(d[c], r[c], accV[c & 3]);
+            accK[c + 1] = __builtin_fmaf(d[c + 1], u[c + 1], accK[c + 1]);
+            q1 = __builtin_fmaf(d[c + 1], u[c + 1], q1);
+            accV[(c + 1) & 3] = __builtin_fmaf(d[c + 1], r[c + 1], accV[(c + 1) & 3]);
+        }
+        accQ[a] += q0 + q1;
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -80,7 +100,7 @@ __device__ __forceinline__ void rc_tile_n(int ni, const float (&fq)[RC_RI], cons
                                           const float *__restrict__ ds_tile, int pitch,
                                           const float *__restrict__ t_tile, size_t t_row, size_t t_key,
                                           const int (&kcol)[RC_RJ],
-                                          float (&accQ)[RC_RI], float (&accK)[RC_RJ], float &accV) {
+                                          float (&accQ)[RC_RI], float (&accK)[RC_RJ], float (&accV)[4]) {
 #define RC_CASE(N) \
     case N: rc_tile<N, MODE>(fq, fk, ds_tile, pitch, t_tile, t_row, t_key, kcol, accQ, accK, accV); break;
     switch (ni) {
@@ -101,7 +121,7 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
     __shared__ float s_fk[2][RC_RJ][64];
     __shared__ float s_sk[2][RC_RJ][64];
     __shared__ int s_kbig[2][RC_RJ];
-    __shared__ float s_ds[2][RC_THREADS];     // dS of the pass rows x tile keys, [row][key]
+    __shared__ __align__(16) float s_ds[2][RC_THREADS];     // dS of the pass rows x tile keys, [row][key]
     __shared__ float s_part[2][RC_W][RC_RJ][64];
     __shared__ float s_dv[RC_W][64];
     __shared__ float s_rowsum;
@@ -136,7 +156,7 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
     }
 
     RC_STAMP(1);
-    float accV = 0.f;
+    float accV[4] = {0.f, 0.f, 0.f, 0.f};
     if (L > 0) {
         const T *qb = Qp + (size_t)b * Tq * H;
         const T *kb = Kp + (size_t)b * Tk * H;
@@ -250,7 +270,7 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
 
     RC_STAMP(3);
     // dv partial of this sample: sum dS t = sum dS - 2 sum dS r
-    s_dv[w][lane] = accV;
+    s_dv[w][lane] = (accV[0] + accV[1]) + (accV[2] + accV[3]);
     __syncthreads();
     if (w == 0) {
         if (hv) {
