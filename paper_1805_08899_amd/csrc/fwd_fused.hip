@@ -117,9 +117,9 @@ struct KeyStream {
 
 // One pass of one wave: NJ keys starting at column jcol0 of the score tile, all rows of the block, all slices
 // of h, factor path only.  s_e: LDS rows of exp(2q), pitch Hp.  NI > 0: exactly NI rows are live, known at
-// compile time (no per-row branches, the next row's LDS read is issued a row ahead); NI == 0: the first ni.  Per row the 4 NJ evaluations
-// are issued as three batches (multiply-adds, reciprocals, accumulations) so that no instruction waits for the
-// one before it.  Returns true if a key value was beyond the factor limit, in which case nothing was written
+// compile time (no per-row branches, the next row's LDS read is issued a row ahead); NI == 0: the first ni.
+// The evaluations of a row are issued in batches (multiply-adds, reciprocals, accumulations) so that no
+// instruction waits for the one before it.  Returns true if a key value was beyond the factor limit, in which case nothing was written
 // and the caller must redo the pass exactly.
 template <typename T, int NG, int NJ, int NI>
 __device__ __forceinline__ bool fw_pass(const float *__restrict__ s_e, int Hp, int ni, KeyStream<T> &ks,
@@ -164,22 +164,26 @@ __device__ __forceinline__ bool fw_pass(const float *__restrict__ s_e, int Hp, i
                 } else {
                     fq = *reinterpret_cast<const float4 *>(e_col + a * Hp);
                 }
-                float t[4][NJ];
+                // two batches of 2 NJ evaluations each: multiply-adds, reciprocals, accumulations
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
+                for (int q0 = 0; q0 < 4; q0 += 2) {
+                    float t[2][NJ];
 #pragma unroll
-                    for (int c = 0; c < NJ; ++c) t[q][c] = __builtin_fmaf(comp(fq, q), fk[q][c], 1.0f);
-                __builtin_amdgcn_sched_barrier(0);
+                    for (int q = 0; q < 2; ++q)
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
+                        for (int c = 0; c < NJ; ++c) t[q][c] = __builtin_fmaf(comp(fq, q0 + q), fk[q0 + q][c], 1.0f);
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int c = 0; c < NJ; ++c) t[q][c] = fast_rcp(t[q][c]);
-                __builtin_amdgcn_sched_barrier(0);
+                    for (int q = 0; q < 2; ++q)
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
+                        for (int c = 0; c < NJ; ++c) t[q][c] = fast_rcp(t[q][c]);
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int c = 0; c < NJ; ++c) acc[a][c] = __builtin_fmaf(vv[q], t[q][c], acc[a][c]);
-                __builtin_amdgcn_sched_barrier(0);
+                    for (int q = 0; q < 2; ++q)
+#pragma unroll
+                        for (int c = 0; c < NJ; ++c) acc[a][c] = __builtin_fmaf(vv[q0 + q], t[q][c], acc[a][c]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
         }
     }

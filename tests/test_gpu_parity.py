@@ -59,6 +59,13 @@ EDGE = [
     ("many_key_tiles", 1, 9, 1100, 64, 8, "f32", [1100]),
     ("bf16_ragged", 3, 21, 34, 130, 20, "bf16", None),
     ("bf16_empty_sample", 2, 6, 7, 16, 16, "bf16", [0, 7]),
+    # placement paths: the forward kernel ranks samples only up to 128 per batch, the backward up to 1024
+    ("batch_beyond_forward_ranking", 131, 5, 9, 32, 8, "f32", None),
+    ("batch_beyond_backward_ranking", 1030, 3, 5, 16, 4, "f32", None),
+    # short key axis with value width beyond one round of the dS kernel, and a key axis just past its limit
+    ("wide_values_short_keys", 2, 20, 40, 64, 1040, "f32", None),
+    ("keys_just_past_the_short_path", 2, 18, 129, 64, 24, "f32", None),
+    ("fused_forward_h_not_multiple_of_256", 3, 11, 13, 300, 12, "f32", None),
 ]
 
 
