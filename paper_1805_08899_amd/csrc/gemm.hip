@@ -335,8 +335,8 @@ __device__ __forceinline__ void rank_block(const int *__restrict__ key_len, int 
 }
 
 // Everything the backward pass needs before the recomputation, in one launch:
-// block 0 ranks the samples, the next nS blocks produce dS (B1 + B2), the
-// rest produce dV (B1).  The three kinds of block do not depend on each other.
+// blocks that produce dS (B1 + B2), blocks that produce dV (B1) and one block
+// that ranks the samples.  The three kinds of block do not depend on each other.
 template <typename TV>
 __global__ __launch_bounds__(256, 3) void k_bwd_pre(const float *__restrict__ dC, const TV *__restrict__ V,
                                                  const float *__restrict__ P, const int *__restrict__ key_len,
@@ -346,28 +346,34 @@ __global__ __launch_bounds__(256, 3) void k_bwd_pre(const float *__restrict__ dC
                                                  int Tq, int Tk, int Dv, int pitch, int s_tiles, int v_xt, int v_yt) {
     extern __shared__ float s_dp[];           // [16][pitch16], four such planes when Tk <= kDsplitMaxTk
     __shared__ int s_len[kMaxSortedB];
-    int bid = blockIdx.x;
     PRE_STAMP(0);
-    if (bid == 0) {
+    // The hardware deals blocks to the eight XCDs round-robin, so block id mod 8 names the XCD.  Sample b is
+    // worked on by XCD b mod 8 only: its dC, V and P then pass through one L2 instead of eight.  Within an XCD the
+    // long dS blocks of all its samples come first, then the dV blocks; the last block of the grid ranks.
+    constexpr int kXcd = 8;
+    const int spx = (B + kXcd - 1) / kXcd;                     // sample slots per XCD
+    const int per_b = v_xt * v_yt;
+    const int per_xcd = spx * (s_tiles + per_b);
+    if ((int)blockIdx.x == kXcd * per_xcd) {
         rank_block(key_len, order, s_len, B, Tk, sorted, fold);
         PRE_STAMP(1);
         return;
     }
-    bid -= 1;
-    const int nS = s_tiles * B;
-    if (bid < nS) {
+    const int xcd = blockIdx.x % kXcd;
+    int li = blockIdx.x / kXcd;
+    if (li < spx * s_tiles) {
+        const int b = xcd + kXcd * (li / s_tiles), i0 = (li % s_tiles) * 16;
+        if (b >= B) return;
         if (Tk <= kDsplitMaxTk)
-            dscore_block_dsplit<TV>(dC, V, P, key_len, dS, ds_rowsum, s_dp, bid / s_tiles, (bid % s_tiles) * 16, Tq,
-                                    Tk, Dv, pitch);
+            dscore_block_dsplit<TV>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
         else
-            dscore_block<TV>(dC, V, P, key_len, dS, ds_rowsum, s_dp, bid / s_tiles, (bid % s_tiles) * 16, Tq, Tk, Dv,
-                             pitch);
+            dscore_block<TV>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
         PRE_STAMP(1);
         return;
     }
-    bid -= nS;
-    const int per_b = v_xt * v_yt;
-    const int b = bid / per_b, rem = bid % per_b;
+    li -= spx * s_tiles;
+    const int b = xcd + kXcd * (li / per_b), rem = li % per_b;
+    if (b >= B) return;
     pv_block<float, true>(P, dC, key_len, dV, Tq, Tk, Dv, b, rem / v_xt, rem % v_xt);
     PRE_STAMP(1);
 }
@@ -379,7 +385,7 @@ hipError_t launch_bwd_pre(const AttnShape &s, const float *dC, const void *V, co
     const int fold = (sorted && (long long)s.B * n_hs <= 512) ? 1 : 0;   // recompute grid in one round
     const int s_tiles = (s.Tq + 15) / 16;
     const int v_xt = (s.Dv + 255) / 256, v_yt = (s.Tk + 15) / 16;
-    const long long blocks = 1 + (long long)s.B * s_tiles + (long long)s.B * v_xt * v_yt;
+    const long long blocks = 1 + 8LL * ((s.B + 7) / 8) * (s_tiles + (long long)v_xt * v_yt);
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     const int pitch16 = (s.Tk + 15) / 16 * 16 + 4;
     const size_t lds = (size_t)(s.Tk <= kDsplitMaxTk ? 4 : 1) * 16 * pitch16 * sizeof(float);
