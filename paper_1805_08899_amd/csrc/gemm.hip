@@ -124,36 +124,66 @@ __device__ __forceinline__ void dscore_block(const float *__restrict__ dC, const
     const float *dCb = dC + (size_t)b * Tq * Dv;
     const TV *Vb = V + (size_t)b * Tk * Dv;
 
+    // Wave w takes key tiles w, w+4, ..., four at a time so that one fragment of dC feeds four products (the
+    // kernel is bound by what the L1 can deliver, not by the matrix cores).  The sum over d runs in stages of U
+    // 16-wide slices; the loads of the next stage are in flight while the current one is multiplied.  Rows and
+    // keys past the end are clamped for loading; what they produce is never read.  Columns past Dv are zeroed.
     const int n_jt = (L + 15) / 16;
-    for (int jt = w; jt < n_jt; jt += 4) {
-        const int i = i0 + lm, j = jt * 16 + lm;
-        const bool iok = i < Tq, jok = j < L;
-        f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
-        constexpr int U = 8;                      // 16-wide slices of d whose loads are in flight together
-        for (int db0 = 0; db0 < Dv; db0 += 16 * U) {
-            float4 a[U], bv[U];
+    constexpr int U = 2, G = 4;
+    const int n_st = (Dv + 16 * U - 1) / (16 * U);            // stages
+    const bool ragged = Dv % (16 * U) != 0;
+    const float *dCrow = dCb + (size_t)min(i0 + lm, Tq - 1) * Dv;
+    for (int jt0 = w; jt0 < n_jt; jt0 += 4 * G) {              // this wave's tiles jt0, jt0 + 4, jt0 + 8, jt0 + 12
+        const TV *vrow[G];
+#pragma unroll
+        for (int k = 0; k < G; ++k) vrow[k] = Vb + (size_t)min((jt0 + 4 * k) * 16 + lm, Tk - 1) * Dv;
+        float4 a[U], bv[G][U], an[U], bn[G][U];
+        auto load = [&](float4 (&da)[U], float4 (&db)[G][U], int st) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int d = db0 + 16 * u + 4 * lk;
-                a[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-                bv[u] = a[u];
-                if (d < Dv) {
-                    if (iok) a[u] = ld4(dCb, (size_t)i * Dv + d);
-                    if (jok) bv[u] = ld4(Vb, (size_t)j * Dv + d);
-                }
+                const int d = min((st * U + u) * 16 + 4 * lk, Dv - 4);
+                da[u] = ld4(dCrow, (size_t)d);
+#pragma unroll
+                for (int k = 0; k < G; ++k) db[k][u] = ld4(vrow[k], (size_t)d);
+            }
+        };
+        load(a, bv, 0);
+        f32x4 acc[G];
+#pragma unroll
+        for (int k = 0; k < G; ++k) acc[k] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int st = 0; st < n_st; ++st) {
+            load(an, bn, min(st + 1, n_st - 1));
+            if (ragged && st == n_st - 1) {                      // columns past Dv add nothing
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if ((st * U + u) * 16 + 4 * lk >= Dv) a[u] = make_float4(0.f, 0.f, 0.f, 0.f);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (db0 + 16 * u < Dv) {
-                    acc = mfma16(a[u].x, bv[u].x, acc);
-                    acc = mfma16(a[u].y, bv[u].y, acc);
-                    acc = mfma16(a[u].z, bv[u].z, acc);
-                    acc = mfma16(a[u].w, bv[u].w, acc);
-                }
+#pragma unroll
+                for (int k = 0; k < G; ++k) acc[k] = mfma16(a[u].x, bv[k][u].x, acc[k]);
+#pragma unroll
+                for (int k = 0; k < G; ++k) acc[k] = mfma16(a[u].y, bv[k][u].y, acc[k]);
+#pragma unroll
+                for (int k = 0; k < G; ++k) acc[k] = mfma16(a[u].z, bv[k][u].z, acc[k]);
+#pragma unroll
+                for (int k = 0; k < G; ++k) acc[k] = mfma16(a[u].w, bv[k][u].w, acc[k]);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                a[u] = an[u];
+#pragma unroll
+                for (int k = 0; k < G; ++k) bv[k][u] = bn[k][u];
             }
         }
 #pragma unroll
-        for (int r = 0; r < 4; ++r) s_dp[(4 * lk + r) * pitch16 + jt * 16 + lm] = acc[r];
+        for (int k = 0; k < G; ++k) {
+            const int jt = jt0 + 4 * k;
+            if (jt < n_jt) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) s_dp[(4 * lk + r) * pitch16 + jt * 16 + lm] = acc[k][r];
+            }
+        }
     }
     __syncthreads();
 
