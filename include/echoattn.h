@@ -101,6 +101,19 @@ echo_status_t echo_attn_bwd(const echo_attn_desc_t *desc,
                             float *dQp, float *dKp, float *dV, float *dv,
                             void *workspace, size_t workspace_bytes, void *stream);
 
+/* Backward of one decoder step (Section 2: the decoder produces one query at a time against the same encoder
+ * states, so Kp, V and v are shared by all steps of a sentence and their gradients are sums over the steps).
+ * Same as echo_attn_bwd, except that dKp, dV and dv are ADDED TO instead of overwritten: the caller clears them
+ * before the first step (rows at masked keys then stay exact zeros) and calls this once per step, with that
+ * step's Qp [B,Tq,H], P and dContext (Tq is usually 1), in any order.  dQp [B,Tq,H] is overwritten.
+ * The result after all steps equals echo_attn_bwd on the steps stacked along Tq, up to the order of additions. */
+echo_status_t echo_attn_bwd_accumulate(const echo_attn_desc_t *desc,
+                                       const float *dContext, const float *P,
+                                       const void *Qp, const void *Kp, const void *V, const void *v,
+                                       const int32_t *key_len,
+                                       float *dQp, float *dKp, float *dV, float *dv,
+                                       void *workspace, size_t workspace_bytes, void *stream);
+
 /* Comparison only: the baseline behaviour of Section 4.1, which stashes the
  * output of tanh as a feature map.  Same results as the pair above;
  * `tanh_map` is B*Tq*Tk*H fp32 (echo_attn_stash_bytes), written by the

@@ -38,6 +38,7 @@ EXPORTS = {
     "echo_attn_stash_bytes": (c_size_t, [POINTER(echo_attn_desc_t)]),
     "echo_attn_fwd": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 8 + [c_size_t, c_void_p]),
     "echo_attn_bwd": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 12 + [c_size_t, c_void_p]),
+    "echo_attn_bwd_accumulate": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 12 + [c_size_t, c_void_p]),
     "echo_attn_fwd_stash": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 9 + [c_size_t, c_void_p]),
     "echo_attn_bwd_stash": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 11 + [c_size_t, c_void_p]),
     "echo_attn_profile_enable": (None, [c_int]),
@@ -121,6 +122,13 @@ def echo_attn_bwd(desc, dContext, P, Qp, Kp, V, v, key_len, dQp, dKp, dV, dv, wo
     return lib().echo_attn_bwd(ctypes.byref(desc), _ptr(dContext), _ptr(P), _ptr(Qp), _ptr(Kp), _ptr(V), _ptr(v),
                                _ptr(key_len), _ptr(dQp), _ptr(dKp), _ptr(dV), _ptr(dv), _ptr(workspace),
                                _ws_bytes(workspace, workspace_bytes), _stream(stream))
+
+
+def echo_attn_bwd_accumulate(desc, dContext, P, Qp, Kp, V, v, key_len, dQp, dKp, dV, dv, workspace,
+                             workspace_bytes=None, stream=None) -> int:
+    return lib().echo_attn_bwd_accumulate(ctypes.byref(desc), _ptr(dContext), _ptr(P), _ptr(Qp), _ptr(Kp), _ptr(V),
+                                          _ptr(v), _ptr(key_len), _ptr(dQp), _ptr(dKp), _ptr(dV), _ptr(dv),
+                                          _ptr(workspace), _ws_bytes(workspace, workspace_bytes), _stream(stream))
 
 
 def echo_attn_fwd_stash(desc, Qp, Kp, V, v, key_len, context, P, tanh_map, workspace, workspace_bytes=None,

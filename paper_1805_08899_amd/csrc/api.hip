@@ -32,7 +32,7 @@ echo_status_t check_desc(const echo_attn_desc_t *d, AttnShape *s) {
     // the 4-D map index B*Tq*Tk*H must fit 62 bits (it always does once the lines above hold; kept explicit)
     const long double n4 = (long double)d->B * d->Tq * d->Tk * d->H;
     if (n4 >= 4.6e18L) return ECHO_ERR_SHAPE;
-    if (s) *s = AttnShape{d->B, d->Tq, d->Tk, d->H, d->Dv, d->in_dtype == ECHO_BF16};
+    if (s) *s = AttnShape{d->B, d->Tq, d->Tk, d->H, d->Dv, d->in_dtype == ECHO_BF16, false};
     return ECHO_OK;
 }
 
@@ -117,12 +117,13 @@ echo_status_t fwd_impl(const echo_attn_desc_t *desc, const void *Qp, const void 
 }
 
 echo_status_t bwd_impl(const echo_attn_desc_t *desc, const float *dContext, const float *P, const float *tmap,
-                       bool use_map, const void *Qp, const void *Kp, const void *V, const void *v,
+                       bool use_map, bool accumulate, const void *Qp, const void *Kp, const void *V, const void *v,
                        const int32_t *key_len, float *dQp, float *dKp, float *dV, float *dv, void *workspace,
                        size_t workspace_bytes, void *stream) {
     AttnShape s;
     echo_status_t rc = check_desc(desc, &s);
     if (rc != ECHO_OK) return rc;
+    s.acc = accumulate;
     if (!dContext || !P || !V || !v || !key_len || !dQp || !dKp || !dV || !dv || !workspace) return ECHO_ERR_NULL;
     if (use_map ? !tmap : (!Qp || !Kp)) return ECHO_ERR_NULL;
     const void *ptrs[] = {dContext, P, tmap, Qp, Kp, V, v, key_len, dQp, dKp, dV, dv, workspace};
@@ -174,7 +175,15 @@ echo_status_t echo_attn_bwd(const echo_attn_desc_t *desc, const float *dContext,
                             const void *Kp, const void *V, const void *v, const int32_t *key_len, float *dQp,
                             float *dKp, float *dV, float *dv, void *workspace, size_t workspace_bytes,
                             void *stream) {
-    return bwd_impl(desc, dContext, P, nullptr, false, Qp, Kp, V, v, key_len, dQp, dKp, dV, dv, workspace,
+    return bwd_impl(desc, dContext, P, nullptr, false, false, Qp, Kp, V, v, key_len, dQp, dKp, dV, dv, workspace,
+                    workspace_bytes, stream);
+}
+
+echo_status_t echo_attn_bwd_accumulate(const echo_attn_desc_t *desc, const float *dContext, const float *P,
+                                       const void *Qp, const void *Kp, const void *V, const void *v,
+                                       const int32_t *key_len, float *dQp, float *dKp, float *dV, float *dv,
+                                       void *workspace, size_t workspace_bytes, void *stream) {
+    return bwd_impl(desc, dContext, P, nullptr, false, true, Qp, Kp, V, v, key_len, dQp, dKp, dV, dv, workspace,
                     workspace_bytes, stream);
 }
 
@@ -188,7 +197,7 @@ echo_status_t echo_attn_bwd_stash(const echo_attn_desc_t *desc, const float *dCo
                                   const float *tanh_map, const void *V, const void *v, const int32_t *key_len,
                                   float *dQp, float *dKp, float *dV, float *dv, void *workspace,
                                   size_t workspace_bytes, void *stream) {
-    return bwd_impl(desc, dContext, P, tanh_map, true, nullptr, nullptr, V, v, key_len, dQp, dKp, dV, dv,
+    return bwd_impl(desc, dContext, P, tanh_map, true, false, nullptr, nullptr, V, v, key_len, dQp, dKp, dV, dv,
                     workspace, workspace_bytes, stream);
 }
 

@@ -28,7 +28,7 @@ __device__ __forceinline__ f32x4 mfma16(float a, float b, f32x4 c) {
 template <typename TB, bool TRANS_A>
 __device__ __forceinline__ void pv_block(const float *__restrict__ P, const TB *__restrict__ Bm,
                                          const int *__restrict__ key_len, float *__restrict__ out,
-                                         int Tq, int Tk, int N, int b, int by, int bx) {
+                                         int Tq, int Tk, int N, int b, int by, int bx, int acc_out) {
     const int L = clamp_len(key_len[b], Tk);
     const int lane = lane_id(), w = wave_id();
     const int M = TRANS_A ? Tk : Tq;
@@ -81,7 +81,15 @@ __device__ __forceinline__ void pv_block(const float *__restrict__ P, const TB *
         const int m = m0 + 4 * lk + r;
         if (m < M) {
             float4 o = make_float4(acc[0][r], acc[1][r], acc[2][r], acc[3][r]);
-            *reinterpret_cast<float4 *>(ob + (size_t)m * N + ncol) = o;
+            float4 *dst = reinterpret_cast<float4 *>(ob + (size_t)m * N + ncol);
+            if (acc_out) {                       // add to what the earlier decoder steps left
+                const float4 old = *dst;
+                o.x += old.x;
+                o.y += old.y;
+                o.z += old.z;
+                o.w += old.w;
+            }
+            *dst = o;
         }
     }
 }
@@ -90,7 +98,7 @@ template <typename TB, bool TRANS_A>
 __global__ __launch_bounds__(256) void k_pv(const float *__restrict__ P, const TB *__restrict__ Bm,
                                             const int *__restrict__ key_len, float *__restrict__ out,
                                             int Tq, int Tk, int N) {
-    pv_block<TB, TRANS_A>(P, Bm, key_len, out, Tq, Tk, N, blockIdx.z, blockIdx.y, blockIdx.x);
+    pv_block<TB, TRANS_A>(P, Bm, key_len, out, Tq, Tk, N, blockIdx.z, blockIdx.y, blockIdx.x, 0);
 }
 
 hipError_t launch_context(const AttnShape &s, const float *P, const void *V, const int *key_len, float *C,
@@ -373,7 +381,7 @@ __global__ __launch_bounds__(256, 3) void k_bwd_pre(const float *__restrict__ dC
                                                  float *__restrict__ dS, float *__restrict__ ds_rowsum,
                                                  int *__restrict__ order, float *__restrict__ dV, int B, int sorted,
                                                  int fold,
-                                                 int Tq, int Tk, int Dv, int pitch, int s_tiles, int v_xt, int v_yt) {
+                                                 int Tq, int Tk, int Dv, int pitch, int s_tiles, int v_xt, int v_yt, int acc) {
     extern __shared__ float s_dp[];           // [16][pitch16], four such planes when Tk <= kDsplitMaxTk
     __shared__ int s_len[kMaxSortedB];
     PRE_STAMP(0);
@@ -404,7 +412,7 @@ __global__ __launch_bounds__(256, 3) void k_bwd_pre(const float *__restrict__ dC
     li -= spx * s_tiles;
     const int b = xcd + kXcd * (li / per_b), rem = li % per_b;
     if (b >= B) return;
-    pv_block<float, true>(P, dC, key_len, dV, Tq, Tk, Dv, b, rem / v_xt, rem % v_xt);
+    pv_block<float, true>(P, dC, key_len, dV, Tq, Tk, Dv, b, rem / v_xt, rem % v_xt, acc);
     PRE_STAMP(1);
 }
 
@@ -429,11 +437,11 @@ hipError_t launch_bwd_pre(const AttnShape &s, const float *dC, const void *V, co
     if (s.bf16)
         k_bwd_pre<bf16_t><<<(unsigned)blocks, 256, lds, st>>>(dC, (const bf16_t *)V, P, key_len, dS, ds_rowsum, order,
                                                              dV, s.B, sorted, fold, s.Tq, s.Tk, s.Dv,
-                                                             ds_pitch(s.Tk), s_tiles, v_xt, v_yt);
+                                                             ds_pitch(s.Tk), s_tiles, v_xt, v_yt, s.acc ? 1 : 0);
     else
         k_bwd_pre<float><<<(unsigned)blocks, 256, lds, st>>>(dC, (const float *)V, P, key_len, dS, ds_rowsum, order,
                                                             dV, s.B, sorted, fold, s.Tq, s.Tk, s.Dv,
-                                                            ds_pitch(s.Tk), s_tiles, v_xt, v_yt);
+                                                            ds_pitch(s.Tk), s_tiles, v_xt, v_yt, s.acc ? 1 : 0);
     return hipGetLastError();
 }
 

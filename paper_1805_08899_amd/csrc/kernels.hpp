@@ -9,6 +9,7 @@ namespace echo {
 struct AttnShape {
     int B, Tq, Tk, H, Dv;
     bool bf16;   // Qp, Kp, V, v stored as bf16
+    bool acc;    // backward: add into dKp, dV, dv instead of overwriting them (per-step decoder form)
 };
 
 // Row pitch (floats) of the dS workspace: keys rounded up to the key tile of

@@ -115,7 +115,7 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
     const T *__restrict__ Qp, const T *__restrict__ Kp, const T *__restrict__ v,
     const int *__restrict__ order, const float *__restrict__ dS, const float *__restrict__ ds_rowsum,
     const float *__restrict__ tmap, float *__restrict__ dQp, float *__restrict__ dKp, float *__restrict__ dv_part,
-    int Tq, int Tk, int H, int pitch, int rows_per_pass) {
+    int Tq, int Tk, int H, int pitch, int rows_per_pass, int acc) {
     // Key tile staged once per block, double buffered: exp(2k) for the factor
     // path, 2 log2e k for the exact path, and per key a flag "beyond the factor limit".
     __shared__ float s_fk[2][RC_RJ][64];
@@ -140,9 +140,10 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
     float *dQb = dQp + (size_t)b * Tq * H;
     float *dKb = dKp + (size_t)b * Tk * H;
 
-    // masked keys: exact zeros
-    for (int j = L + w; j < Tk; j += RC_W)
-        if (hv) dKb[(size_t)j * H + h] = 0.f;
+    // masked keys: exact zeros (when adding to earlier decoder steps they hold zeros already)
+    if (!acc)
+        for (int j = L + w; j < Tk; j += RC_W)
+            if (hv) dKb[(size_t)j * H + h] = 0.f;
     if (L == 0) {                                   // block-uniform
         for (int i = w; i < Tq; i += RC_W)
             if (hv) dQb[(size_t)i * H + h] = 0.f;
@@ -256,7 +257,7 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
                 if (j < L && hv) {
                     float *dst = dKb + (size_t)j * H + h;
                     const float val = v4 * tot;
-                    *dst = (pass == 0) ? val : *dst + val;
+                    *dst = (pass == 0 && !acc) ? val : *dst + val;
                 }
             }
             if (hv) {
@@ -312,11 +313,11 @@ static hipError_t launch_recompute_t(const AttnShape &s, const void *Qp, const v
     if (tmap)
         k_recompute<T, true><<<grid, RC_THREADS, 0, st>>>((const T *)Qp, (const T *)Kp, (const T *)v, order, dS,
                                                           ds_rowsum, tmap, dQp, dKp, dv_part, s.Tq, s.Tk, s.H,
-                                                          ds_pitch(s.Tk), rows_per_pass);
+                                                          ds_pitch(s.Tk), rows_per_pass, s.acc ? 1 : 0);
     else
         k_recompute<T, false><<<grid, RC_THREADS, 0, st>>>((const T *)Qp, (const T *)Kp, (const T *)v, order, dS,
                                                            ds_rowsum, tmap, dQp, dKp, dv_part, s.Tq, s.Tk, s.H,
-                                                           ds_pitch(s.Tk), rows_per_pass);
+                                                           ds_pitch(s.Tk), rows_per_pass, s.acc ? 1 : 0);
     return hipGetLastError();
 }
 

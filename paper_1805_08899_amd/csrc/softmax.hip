@@ -35,11 +35,11 @@ hipError_t launch_softmax(const AttnShape &s, const float *S, const int *key_len
     return hipGetLastError();
 }
 
-// dv[h] = sum_b dv_part[b,h].  Block = 64 values of h x 8 groups of samples:
+// dv[h] = sum_b dv_part[b,h] (added to dv when add_to is set).  Block = 64 values of h x 8 groups of samples:
 // group g adds samples g, g + 8, ... with eight loads in flight at a time, then
 // the groups' sums are added in group order, so the result is reproducible.
 __global__ __launch_bounds__(512) void k_dv_reduce(const float *__restrict__ dv_part, float *__restrict__ dv, int B,
-                                                  int H) {
+                                                  int H, int add_to) {
     __shared__ float s_acc[8][64];
     const int lane = lane_id(), g = wave_id();
     const int h = blockIdx.x * 64 + lane;
@@ -59,12 +59,12 @@ __global__ __launch_bounds__(512) void k_dv_reduce(const float *__restrict__ dv_
         float tot = 0.f;
 #pragma unroll
         for (int k = 0; k < 8; ++k) tot += s_acc[k][lane];
-        dv[h] = tot;
+        dv[h] = add_to ? dv[h] + tot : tot;
     }
 }
 
 hipError_t launch_dv_reduce(const AttnShape &s, const float *dv_part, float *dv, hipStream_t st) {
-    k_dv_reduce<<<(s.H + 63) / 64, 512, 0, st>>>(dv_part, dv, s.B, s.H);
+    k_dv_reduce<<<(s.H + 63) / 64, 512, 0, st>>>(dv_part, dv, s.B, s.H, s.acc ? 1 : 0);
     return hipGetLastError();
 }
 

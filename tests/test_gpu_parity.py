@@ -129,3 +129,51 @@ def test_forward_only_and_backward_from_given_P(H):
     got = db.results()
     for k in ("dQp", "dKp", "dV", "dv"):
         assert rel_err(got[k], ref[k]) <= 1e-4, k
+
+
+STEP_CASES = [
+    # name, B, T (decoder steps), Tk, H, Dv, dtype
+    ("steps_tiny", 5, 6, 9, 64, 16, "f32"),
+    ("steps_nmt_like", 16, 7, 50, 512, 512, "f32"),
+    ("steps_bf16", 6, 4, 21, 128, 64, "bf16"),
+]
+
+
+@pytest.mark.parametrize("case", STEP_CASES, ids=[c[0] for c in STEP_CASES])
+def test_decoder_steps_match_the_batched_layer(H, case):
+    """Per-step decoder form: T calls with one query each (forward), then T calls of the accumulating backward,
+    against the oracle run once on the T queries stacked along Tq.  The keys, values and v are shared by the
+    steps, so dKp, dV and dv are sums over the steps."""
+    import torch
+    from paper_1805_08899_amd import binding as eb
+    name, B, T, Tk, Hh, Dv, dt = case
+    print("decoder steps", case, flush=True)
+    wl = Workload(name, B, T, Tk, Hh, Dv, dt, 0.5, 1, Tk, dt == "bf16")
+    inputs = make_inputs(wl, seed=4321 + T)
+    ref = oracle_outputs(inputs, workers=1)
+    full = H.DeviceBatch(wl, inputs)                     # device copies of Kp, V, v, key_len, dC
+    step_desc = eb.make_desc(B, 1, Tk, Hh, Dv, dt)
+    ws = torch.empty(max(eb.echo_attn_fwd_workspace_bytes(step_desc), eb.echo_attn_bwd_workspace_bytes(step_desc), 16),
+                     dtype=torch.uint8, device=full.device)
+    st = torch.cuda.current_stream(full.device)
+    f32 = dict(dtype=torch.float32, device=full.device)
+    # one allocation per step and tensor: the library wants 16-byte aligned pointers
+    ctx = [torch.full((B, 1, Dv), float("nan"), **f32) for _ in range(T)]
+    P = [torch.full((B, 1, Tk), float("nan"), **f32) for _ in range(T)]
+    dQ = [torch.full((B, 1, Hh), float("nan"), **f32) for _ in range(T)]
+    q_steps = [full.Qp[:, t:t + 1, :].contiguous() for t in range(T)]
+    dc_steps = [full.dC[:, t:t + 1, :].contiguous() for t in range(T)]
+    for t in range(T):
+        eb.check(eb.echo_attn_fwd(step_desc, q_steps[t], full.Kp, full.V, full.v, full.key_len, ctx[t], P[t], ws,
+                                  stream=st), "step fwd")
+    dK = torch.zeros(B, Tk, Hh, **f32)
+    dV = torch.zeros(B, Tk, Dv, **f32)
+    dv = torch.zeros(Hh, **f32)
+    for t in reversed(range(T)):                          # back-propagation through time visits the steps in reverse
+        eb.check(eb.echo_attn_bwd_accumulate(step_desc, dc_steps[t], P[t], q_steps[t], full.Kp, full.V, full.v,
+                                             full.key_len, dQ[t], dK, dV, dv, ws, stream=st), "step bwd")
+    torch.cuda.synchronize(full.device)
+    got = {"context": torch.cat(ctx, dim=1).cpu().numpy(), "P": torch.cat(P, dim=1).cpu().numpy(),
+           "dQp": torch.cat(dQ, dim=1).cpu().numpy(), "dKp": dK.cpu().numpy(), "dV": dV.cpu().numpy(),
+           "dv": dv.cpu().numpy()}
+    assert_parity(got, ref, inputs, dt, name)
