@@ -48,6 +48,8 @@ def main() -> int:
     ap.add_argument("--workload", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stash", action="store_true")
+    ap.add_argument("--decoder-steps", action="store_true",
+                    help="also time the per-step decoder form of the same workload (Tq calls with one query each)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (a batch shards over samples, "
@@ -180,6 +182,7 @@ def main() -> int:
         del dbs
         torch.cuda.empty_cache()
 
+    decoder = decoder_steps(eb, harness, torch, wl, inputs, dev) if args.decoder_steps else None
     cpu = None if args.no_cpu_baseline else cpu_baseline(wl, inputs)
 
     out = {
@@ -201,6 +204,7 @@ def main() -> int:
         "measured_ceilings": cal,
         "peak_bytes": peak,
         "stash_variant_ms": stash_timing,
+        "decoder_steps": decoder,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
@@ -239,6 +243,61 @@ def calibrate(eb, torch, dev):
     dst = torch.empty(n, dtype=torch.uint8, device=dev)
     out["copy_read_plus_write_bytes_per_s"] = 2 * run(eb.ECHO_CAL_COPY, src=src, dst=dst, nbytes=n)
     return out
+
+
+def decoder_steps(eb, harness, torch, wl, inputs, dev, reps=20):
+    """The same batch as Tq decoder steps of one query each (the shape the translation model's decoder produces):
+    Tq forward calls, then Tq accumulating backward calls; launched one by one and replayed from a HIP graph."""
+    full = harness.DeviceBatch(wl, inputs, device=dev)
+    T = wl.Tq
+    desc = eb.make_desc(wl.B, 1, wl.Tk, wl.H, wl.Dv, wl.in_dtype)
+    ws = torch.empty(max(eb.echo_attn_fwd_workspace_bytes(desc), eb.echo_attn_bwd_workspace_bytes(desc), 16),
+                     dtype=torch.uint8, device=dev)
+    f32 = dict(dtype=torch.float32, device=dev)
+    q = [full.Qp[:, t:t + 1, :].contiguous() for t in range(T)]
+    dc = [full.dC[:, t:t + 1, :].contiguous() for t in range(T)]
+    ctx = [torch.empty(wl.B, 1, wl.Dv, **f32) for _ in range(T)]
+    P = [torch.empty(wl.B, 1, wl.Tk, **f32) for _ in range(T)]
+    dQ = [torch.empty(wl.B, 1, wl.H, **f32) for _ in range(T)]
+    dK, dV, dv = torch.empty(wl.B, wl.Tk, wl.H, **f32), torch.empty(wl.B, wl.Tk, wl.Dv, **f32), torch.empty(wl.H, **f32)
+
+    def sentence():
+        st = torch.cuda.current_stream(dev)
+        for t in (dK, dV, dv):
+            t.zero_()
+        for t in range(T):
+            eb.check(eb.echo_attn_fwd(desc, q[t], full.Kp, full.V, full.v, full.key_len, ctx[t], P[t], ws, stream=st))
+        for t in reversed(range(T)):
+            eb.check(eb.echo_attn_bwd_accumulate(desc, dc[t], P[t], q[t], full.Kp, full.V, full.v, full.key_len,
+                                                 dQ[t], dK, dV, dv, ws, stream=st))
+
+    def timed(fn):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize(dev)
+        t0 = time.perf_counter()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize(dev)
+        return (time.perf_counter() - t0) * 1e3 / reps, a.elapsed_time(b) / reps
+
+    for _ in range(3):
+        sentence()
+    eager_wall, eager_gpu = timed(sentence)
+    side = torch.cuda.Stream(device=dev)
+    side.wait_stream(torch.cuda.current_stream(dev))
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            sentence()
+    torch.cuda.current_stream(dev).wait_stream(side)
+    graph.replay()
+    graph_wall, graph_gpu = timed(graph.replay)
+    return {"steps": T, "launches_per_sentence": 4 * T + 3,
+            "eager_ms_per_sentence": eager_wall, "eager_gpu_ms_per_sentence": eager_gpu,
+            "graph_ms_per_sentence": graph_wall, "graph_gpu_ms_per_sentence": graph_gpu,
+            "graph_us_per_step_fwd_bwd": 1e3 * graph_gpu / T}
 
 
 def cpu_baseline(wl, inputs):
