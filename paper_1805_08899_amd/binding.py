@@ -1,4 +1,4 @@
-"""ctypes binding of libechoattn: same names as include/echoattn.h, argument
+"""ctypes binding of libechoattn: same names as include/echoattn.h and include/echodropout.h, argument
 marshalling only.  Device buffers are passed as torch tensors (their
 data_ptr() is taken) or as integer addresses; nothing is computed here.
 
@@ -45,6 +45,10 @@ EXPORTS = {
     "echo_attn_profile_read": (c_int, [POINTER(c_char_p), POINTER(c_int), POINTER(c_float), c_int]),
     "echo_attn_calibrate": (c_int, [c_int, c_int, c_int, c_void_p, c_void_p, c_size_t, POINTER(ctypes.c_double),
                                     c_void_p]),
+    "echo_dropout_mask_words": (c_size_t, [c_size_t]),
+    "echo_dropout_fwd": (c_int, [c_void_p, c_size_t, c_float, ctypes.c_uint64, ctypes.c_uint64, c_void_p, c_void_p,
+                                 c_void_p]),
+    "echo_dropout_bwd": (c_int, [c_void_p, c_void_p, c_size_t, c_float, c_void_p, c_void_p]),
     "echo_status_string": (c_char_p, [c_int]),
     "echo_last_error_detail": (c_char_p, []),
     "echo_version": (c_char_p, []),
@@ -167,6 +171,18 @@ def echo_attn_calibrate(kind, blocks, iters, src, dst, nbytes, stream=None):
     st = lib().echo_attn_calibrate(kind, blocks, iters, _ptr(src), _ptr(dst), nbytes, ctypes.byref(work),
                                    _stream(stream))
     return st, work.value
+
+
+def echo_dropout_mask_words(n: int) -> int:
+    return lib().echo_dropout_mask_words(n)
+
+
+def echo_dropout_fwd(x, n, p, seed, offset, y, mask_bits, stream=None) -> int:
+    return lib().echo_dropout_fwd(_ptr(x), n, p, seed, offset, _ptr(y), _ptr(mask_bits), _stream(stream))
+
+
+def echo_dropout_bwd(dy, mask_bits, n, p, dx, stream=None) -> int:
+    return lib().echo_dropout_bwd(_ptr(dy), _ptr(mask_bits), n, p, _ptr(dx), _stream(stream))
 
 
 def echo_status_string(status: int) -> str:

@@ -8,13 +8,16 @@ import pytest
 from paper_1805_08899_amd import binding as eb
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "echoattn.h")
+HEADERS = [os.path.join(ROOT, "include", f) for f in sorted(os.listdir(os.path.join(ROOT, "include")))
+           if f.endswith(".h")]
 
 
 def declared_symbols():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(echo_[a-z_]+)\s*\(", text)))
+    names = set()
+    for h in HEADERS:
+        text = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names |= set(re.findall(r"\b(echo_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
@@ -96,3 +99,15 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(eb, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(FileNotFoundError):
         eb.lib()
+
+
+def test_dropout_rejects_bad_arguments_without_launching():
+    assert eb.echo_dropout_mask_words(1) == 1 and eb.echo_dropout_mask_words(32) == 1
+    assert eb.echo_dropout_mask_words(33) == 2
+    assert eb.echo_dropout_fwd(None, 8, 0.5, 1, 0, A, A) == eb.ECHO_ERR_NULL
+    assert eb.echo_dropout_fwd(A, 0, 0.5, 1, 0, A, A) == eb.ECHO_ERR_SHAPE
+    assert eb.echo_dropout_fwd(A, 8, 1.0, 1, 0, A, A) == eb.ECHO_ERR_SHAPE
+    assert eb.echo_dropout_fwd(A, 8, -0.1, 1, 0, A, A) == eb.ECHO_ERR_SHAPE
+    assert eb.echo_dropout_fwd(A + 4, 8, 0.5, 1, 0, A, A) == eb.ECHO_ERR_ALIGN
+    assert eb.echo_dropout_bwd(A, None, 8, 0.5, A) == eb.ECHO_ERR_NULL
+    assert eb.echo_dropout_bwd(A, A, 8, float("nan"), A) == eb.ECHO_ERR_SHAPE
