@@ -48,6 +48,8 @@ def main() -> int:
     ap.add_argument("--workload", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stash", action="store_true")
+    ap.add_argument("--dropout", action="store_true",
+                    help="also time the one-bit dropout codec (HBM-bound) on 64 Mi elements")
     ap.add_argument("--decoder-steps", action="store_true",
                     help="also time the per-step decoder form of the same workload (Tq calls with one query each)")
     args = ap.parse_args()
@@ -183,6 +185,7 @@ def main() -> int:
         torch.cuda.empty_cache()
 
     decoder = decoder_steps(eb, harness, torch, wl, inputs, dev) if args.decoder_steps else None
+    dropout = dropout_codec(eb, torch, dev, cpu=not args.no_cpu_baseline) if args.dropout else None
     cpu = None if args.no_cpu_baseline else cpu_baseline(wl, inputs)
 
     out = {
@@ -205,6 +208,7 @@ def main() -> int:
         "peak_bytes": peak,
         "stash_variant_ms": stash_timing,
         "decoder_steps": decoder,
+        "dropout_codec": dropout,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
@@ -298,6 +302,49 @@ def decoder_steps(eb, harness, torch, wl, inputs, dev, reps=20):
             "eager_ms_per_sentence": eager_wall, "eager_gpu_ms_per_sentence": eager_gpu,
             "graph_ms_per_sentence": graph_wall, "graph_gpu_ms_per_sentence": graph_gpu,
             "graph_us_per_step_fwd_bwd": 1e3 * graph_gpu / T}
+
+
+def dropout_codec(eb, torch, dev, n=1 << 26, p=0.1, reps=20, cpu=True):
+    """One-bit dropout on n fp32 elements: forward reads x and writes y plus n/8 bytes of mask, backward reads dy
+    and the mask and writes dx: 8.125 algorithmic bytes per element and pass, against the 8 TB/s HBM peak."""
+    x = torch.randn(n, device=dev)
+    y = torch.empty_like(x)
+    dx = torch.empty_like(x)
+    bits = torch.empty(eb.echo_dropout_mask_words(n), dtype=torch.int32, device=dev)
+    st = torch.cuda.current_stream(dev)
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize(dev)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize(dev)
+        return a.elapsed_time(b) * 1e-3 / reps
+
+    t_f = timed(lambda: eb.check(eb.echo_dropout_fwd(x, n, p, 1234, 0, y, bits, stream=st), "echo_dropout_fwd"))
+    t_b = timed(lambda: eb.check(eb.echo_dropout_bwd(y, bits, n, p, dx, stream=st), "echo_dropout_bwd"))
+    nbytes = 8.125 * n
+    out = {"elements": n, "p": p, "bytes_per_element_and_pass": 8.125,
+           "fwd": {"ms": t_f * 1e3, "GB_per_s": nbytes / t_f / 1e9, "frac_of_8TBps": nbytes / t_f / PEAK_HBM},
+           "bwd": {"ms": t_b * 1e3, "GB_per_s": nbytes / t_b / 1e9, "frac_of_8TBps": nbytes / t_b / PEAK_HBM},
+           "feature_map_bytes": {"one_bit": n // 8, "fp32_mask": 4 * n}}
+    if cpu:
+        import numpy as np
+        from oracle import dropout_ref
+        m = 1 << 22
+        xs = x[:m].cpu().numpy()
+        t0 = time.perf_counter()
+        ys, bs = dropout_ref.forward(xs, p, 1234, 0)
+        dropout_ref.backward(ys, bs, p)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": m / dt / 1e9, "unit": "Gelements/s (fwd+bwd)", "cores": 1, "kind": "oracle",
+                               "sample": f"{m} elements, one forward and one backward in NumPy, {dt:.2f} s"}
+        out["gpu_Gelements_per_s_fwd_bwd"] = n / (t_f + t_b) / 1e9
+    return out
 
 
 def cpu_baseline(wl, inputs):
