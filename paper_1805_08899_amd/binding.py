@@ -65,6 +65,13 @@ def lib() -> ctypes.CDLL:
             raise FileNotFoundError(
                 f"{LIB_PATH} is missing: build it with `python -m paper_1805_08899_amd.build` "
                 "(there is no fallback implementation)")
+        try:
+            # The process must end up with ONE HIP runtime.  PyTorch ships its own copy; if this library is
+            # loaded first it pulls in the system's copy and PyTorch then finds no device.  Loading PyTorch first
+            # makes both use PyTorch's.
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = ctypes.CDLL(LIB_PATH)
         for name, (res, args) in EXPORTS.items():
             fn = getattr(L, name)
