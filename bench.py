@@ -50,6 +50,8 @@ def main() -> int:
     ap.add_argument("--no-stash", action="store_true")
     ap.add_argument("--dropout", action="store_true",
                     help="also time the one-bit dropout codec (HBM-bound) on 64 Mi elements")
+    ap.add_argument("--lstm-cell", action="store_true",
+                    help="also time the LSTM cell's non-linear block, recompute against stash (HBM-bound)")
     ap.add_argument("--decoder-steps", action="store_true",
                     help="also time the per-step decoder form of the same workload (Tq calls with one query each)")
     args = ap.parse_args()
@@ -186,6 +188,7 @@ def main() -> int:
 
     decoder = decoder_steps(eb, harness, torch, wl, inputs, dev) if args.decoder_steps else None
     dropout = dropout_codec(eb, torch, dev, cpu=not args.no_cpu_baseline) if args.dropout else None
+    lstm = lstm_cell(eb, torch, dev, cpu=not args.no_cpu_baseline) if args.lstm_cell else None
     cpu = None if args.no_cpu_baseline else cpu_baseline(wl, inputs)
 
     out = {
@@ -209,6 +212,7 @@ def main() -> int:
         "stash_variant_ms": stash_timing,
         "decoder_steps": decoder,
         "dropout_codec": dropout,
+        "lstm_cell": lstm,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
@@ -344,6 +348,70 @@ def dropout_codec(eb, torch, dev, n=1 << 26, p=0.1, reps=20, cpu=True):
         out["cpu_baseline"] = {"value": m / dt / 1e9, "unit": "Gelements/s (fwd+bwd)", "cores": 1, "kind": "oracle",
                                "sample": f"{m} elements, one forward and one backward in NumPy, {dt:.2f} s"}
         out["gpu_Gelements_per_s_fwd_bwd"] = n / (t_f + t_b) / 1e9
+    return out
+
+
+def lstm_cell(eb, torch, dev, shapes=((128, 512), (128, 1024), (16384, 1024)), reps=50, cpu=True):
+    """The LSTM cell's non-linear block.  Algorithmic bytes per element of [B, H]: recompute forward 60 (reads
+    Gx, Gh, c_prev, writes h, c and the kept sum), recompute backward 48 (reads dh, dc, the sum, c_prev, writes
+    da, dc_prev); stash forward 64, stash backward 52.  The first two shapes are one cell of the translation
+    model (a few MB: launch-bound); the third is 128 such cells' worth of rows, to show the HBM rate."""
+    from paper_1805_08899_amd.workloads import make_lstm_inputs
+    st = torch.cuda.current_stream(dev)
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize(dev)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize(dev)
+        return a.elapsed_time(b) * 1e-3 / reps
+
+    out = {"bytes_per_element": {"fwd": 60, "bwd": 48, "fwd_stash": 64, "bwd_stash": 52}, "shapes": []}
+    for B, H in shapes:
+        n = B * H
+        t = {k: torch.randn(B, w * H, device=dev) for k, w in
+             (("Gx", 4), ("Gh", 4), ("c_prev", 1), ("dh", 1), ("dc", 1))}
+        o = {k: torch.empty(B, w * H, device=dev) for k, w in
+             (("h", 1), ("c", 1), ("a", 4), ("da", 4), ("dcp", 1), ("acts", 4), ("tc", 1))}
+        runs = {
+            "fwd": lambda: eb.check(eb.echo_lstm_cell_fwd(B, H, t["Gx"], t["Gh"], t["c_prev"], o["h"], o["c"], o["a"],
+                                                          stream=st), "echo_lstm_cell_fwd"),
+            "bwd": lambda: eb.check(eb.echo_lstm_cell_bwd(B, H, t["dh"], t["dc"], o["a"], t["c_prev"], o["da"],
+                                                          o["dcp"], stream=st), "echo_lstm_cell_bwd"),
+            "fwd_stash": lambda: eb.check(eb.echo_lstm_cell_fwd_stash(B, H, t["Gx"], t["Gh"], t["c_prev"], o["h"],
+                                                                      o["c"], o["acts"], o["tc"], stream=st),
+                                          "echo_lstm_cell_fwd_stash"),
+            "bwd_stash": lambda: eb.check(eb.echo_lstm_cell_bwd_stash(B, H, t["dh"], t["dc"], o["acts"], o["tc"],
+                                                                      t["c_prev"], o["da"], o["dcp"], stream=st),
+                                          "echo_lstm_cell_bwd_stash"),
+        }
+        row = {"B": B, "H": H,
+               "kept_bytes": {"recompute": eb.echo_lstm_cell_kept_bytes(B, H, False),
+                              "stash": eb.echo_lstm_cell_kept_bytes(B, H, True)}}
+        for k, fn in runs.items():
+            dt = timed(fn)
+            nbytes = out["bytes_per_element"][k] * n
+            row[k] = {"us": dt * 1e6, "GB_per_s": nbytes / dt / 1e9, "frac_of_8TBps": nbytes / dt / PEAK_HBM}
+        out["shapes"].append(row)
+        del t, o
+    if cpu:
+        from oracle import lstm_ref
+        B, H = 2048, 1024
+        inp = make_lstm_inputs(B, H, seed=0)
+        t0 = time.perf_counter()
+        _, _, a = lstm_ref.forward(inp["Gx"], inp["Gh"], inp["c_prev"])
+        lstm_ref.backward(inp["dh"], inp["dc"], a, inp["c_prev"])
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": B * H / dt / 1e9, "unit": "Gelements/s (fwd+bwd)", "cores": 1,
+                               "kind": "oracle",
+                               "sample": f"B={B}, H={H}, one forward and one backward in float64 NumPy, {dt:.2f} s"}
+        big = out["shapes"][-1]
+        out["gpu_Gelements_per_s_fwd_bwd"] = big["B"] * big["H"] / ((big["fwd"]["us"] + big["bwd"]["us"]) * 1e-6) / 1e9
     return out
 
 

@@ -1,5 +1,5 @@
-"""ctypes binding of libechoattn: same names as include/echoattn.h and include/echodropout.h, argument
-marshalling only.  Device buffers are passed as torch tensors (their
+"""ctypes binding of libechoattn: same names as include/echoattn.h, include/echodropout.h and
+include/echolstm.h, argument marshalling only.  Device buffers are passed as torch tensors (their
 data_ptr() is taken) or as integer addresses; nothing is computed here.
 
 The shared library must have been built (python -m paper_1805_08899_amd.build);
@@ -49,6 +49,11 @@ EXPORTS = {
     "echo_dropout_fwd": (c_int, [c_void_p, c_size_t, c_float, ctypes.c_uint64, ctypes.c_uint64, c_void_p, c_void_p,
                                  c_void_p]),
     "echo_dropout_bwd": (c_int, [c_void_p, c_void_p, c_size_t, c_float, c_void_p, c_void_p]),
+    "echo_lstm_cell_fwd": (c_int, [ctypes.c_int64, ctypes.c_int64] + [c_void_p] * 7),
+    "echo_lstm_cell_bwd": (c_int, [ctypes.c_int64, ctypes.c_int64] + [c_void_p] * 7),
+    "echo_lstm_cell_fwd_stash": (c_int, [ctypes.c_int64, ctypes.c_int64] + [c_void_p] * 8),
+    "echo_lstm_cell_bwd_stash": (c_int, [ctypes.c_int64, ctypes.c_int64] + [c_void_p] * 8),
+    "echo_lstm_cell_kept_bytes": (c_size_t, [ctypes.c_int64, ctypes.c_int64, c_int]),
     "echo_status_string": (c_char_p, [c_int]),
     "echo_last_error_detail": (c_char_p, []),
     "echo_version": (c_char_p, []),
@@ -190,6 +195,30 @@ def echo_dropout_fwd(x, n, p, seed, offset, y, mask_bits, stream=None) -> int:
 
 def echo_dropout_bwd(dy, mask_bits, n, p, dx, stream=None) -> int:
     return lib().echo_dropout_bwd(_ptr(dy), _ptr(mask_bits), n, p, _ptr(dx), _stream(stream))
+
+
+def echo_lstm_cell_fwd(B, H, Gx, Gh, c_prev, h, c, a, stream=None) -> int:
+    return lib().echo_lstm_cell_fwd(B, H, _ptr(Gx), _ptr(Gh), _ptr(c_prev), _ptr(h), _ptr(c), _ptr(a),
+                                    _stream(stream))
+
+
+def echo_lstm_cell_bwd(B, H, dh, dc, a, c_prev, da, dc_prev, stream=None) -> int:
+    return lib().echo_lstm_cell_bwd(B, H, _ptr(dh), _ptr(dc), _ptr(a), _ptr(c_prev), _ptr(da), _ptr(dc_prev),
+                                    _stream(stream))
+
+
+def echo_lstm_cell_fwd_stash(B, H, Gx, Gh, c_prev, h, c, acts, tanh_c, stream=None) -> int:
+    return lib().echo_lstm_cell_fwd_stash(B, H, _ptr(Gx), _ptr(Gh), _ptr(c_prev), _ptr(h), _ptr(c), _ptr(acts),
+                                          _ptr(tanh_c), _stream(stream))
+
+
+def echo_lstm_cell_bwd_stash(B, H, dh, dc, acts, tanh_c, c_prev, da, dc_prev, stream=None) -> int:
+    return lib().echo_lstm_cell_bwd_stash(B, H, _ptr(dh), _ptr(dc), _ptr(acts), _ptr(tanh_c), _ptr(c_prev),
+                                          _ptr(da), _ptr(dc_prev), _stream(stream))
+
+
+def echo_lstm_cell_kept_bytes(B: int, H: int, stash: bool) -> int:
+    return lib().echo_lstm_cell_kept_bytes(B, H, 1 if stash else 0)
 
 
 def echo_status_string(status: int) -> str:

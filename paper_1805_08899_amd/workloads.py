@@ -94,3 +94,19 @@ def make_inputs(wl: Workload, seed: int | None = None, *, B: int | None = None) 
             out[k + "_bits"] = bits
             out[k] = bf16_bits_to_f32(bits)
     return out
+
+
+def make_lstm_inputs(B: int, H: int, seed: int, scale: float = 1.0) -> Dict[str, np.ndarray]:
+    """One LSTM cell's worth of inputs (Section 2: two fully-connected outputs of four times the hidden size,
+    the previous cell state) and the two upstream gradients.  Draw order: Gx, Gh, c_prev, dh, dc; float32.
+    The translation model of the paper runs its cells at batch size 128 (Section 6.2); the pre-activations of a
+    trained cell are of order one, which `scale` = 1 stands in for."""
+    rng = np.random.default_rng(SEED_BASE + 1000 + seed)
+    f32 = np.float32
+    return {
+        "Gx": (rng.standard_normal((B, 4 * H)) * scale).astype(f32),
+        "Gh": (rng.standard_normal((B, 4 * H)) * scale).astype(f32),
+        "c_prev": rng.standard_normal((B, H)).astype(f32),
+        "dh": rng.standard_normal((B, H)).astype(f32),
+        "dc": rng.standard_normal((B, H)).astype(f32),
+    }

@@ -111,3 +111,18 @@ def test_dropout_rejects_bad_arguments_without_launching():
     assert eb.echo_dropout_fwd(A + 4, 8, 0.5, 1, 0, A, A) == eb.ECHO_ERR_ALIGN
     assert eb.echo_dropout_bwd(A, None, 8, 0.5, A) == eb.ECHO_ERR_NULL
     assert eb.echo_dropout_bwd(A, A, 8, float("nan"), A) == eb.ECHO_ERR_SHAPE
+
+
+def test_lstm_cell_rejects_bad_arguments_without_launching():
+    assert eb.echo_lstm_cell_kept_bytes(128, 512, False) == 5 * 128 * 512 * 4
+    assert eb.echo_lstm_cell_kept_bytes(128, 512, True) == 6 * 128 * 512 * 4
+    assert eb.echo_lstm_cell_kept_bytes(0, 512, True) == 0
+    assert eb.echo_lstm_cell_fwd(4, 8, A, None, A, A, A, A) == eb.ECHO_ERR_NULL
+    assert eb.echo_lstm_cell_fwd(0, 8, A, A, A, A, A, A) == eb.ECHO_ERR_SHAPE
+    assert eb.echo_lstm_cell_fwd(4, -1, A, A, A, A, A, A) == eb.ECHO_ERR_SHAPE
+    assert eb.echo_lstm_cell_fwd(1 << 30, 1 << 30, A, A, A, A, A, A) == eb.ECHO_ERR_SHAPE
+    assert eb.echo_lstm_cell_fwd(4, 8, A, A, A + 4, A, A, A) == eb.ECHO_ERR_ALIGN
+    assert eb.echo_lstm_cell_bwd(4, 8, None, A, A, A, A, A) == eb.ECHO_ERR_NULL
+    assert eb.echo_lstm_cell_bwd(4, 8, A, A + 8, A, A, A, A) == eb.ECHO_ERR_ALIGN
+    assert eb.echo_lstm_cell_fwd_stash(4, 8, A, A, A, A, A, A, None) == eb.ECHO_ERR_NULL
+    assert eb.echo_lstm_cell_bwd_stash(4, 8, A, A, A, None, A, A, A) == eb.ECHO_ERR_NULL
