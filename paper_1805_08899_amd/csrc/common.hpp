@@ -127,4 +127,15 @@ __device__ __forceinline__ float wave_transpose_sum(float (&a)[N]) {
 
 __device__ __forceinline__ int clamp_len(int len, int Tk) { return len < 0 ? 0 : (len > Tk ? Tk : len); }
 
+// n items dealt to the 8 waves of a block as contiguous ranges of n / 8 or n / 8 + 1 items: first item of wave w
+// (w = 8 gives n).  Waves w and w + 4 run on the same SIMD, so the n % 8 longer ranges go to waves
+// 0, 5, 2, 7, 4, 1, 6, 3 in that order: the SIMDs' totals then differ by at most one item, where the plain
+// floor(n w / 8) split would hand both longer ranges of n % 8 == 2 to one SIMD.
+__device__ __forceinline__ int deal8_begin(int n, int w) {
+    // kLonger[e]: bit w set if wave w gets a longer range when n % 8 == e
+    constexpr unsigned kLonger[8] = {0x00u, 0x01u, 0x21u, 0x25u, 0xa5u, 0xb5u, 0xb7u, 0xf7u};
+    const unsigned m = kLonger[n & 7];
+    return (n >> 3) * w + __builtin_popcount(m & ((1u << w) - 1u));
+}
+
 }  // namespace echo

@@ -5,7 +5,7 @@
 //
 // Block = (sample b, up to RT = 8 NG query rows), 8 waves.
 //   A  exp(2q) of the rows goes to LDS (taken once per block).
-//   B  the valid keys are dealt to the waves in eight contiguous, equal shares;
+//   B  the valid keys are dealt to the waves in eight contiguous shares that differ by at most one key;
 //      a wave walks its share in passes of up to four keys.  A lane owns four
 //      consecutive h of every 256-wide slice, so a key row arrives as one
 //      16-byte load per lane (every K element is exponentiated once per block)
@@ -50,7 +50,7 @@ __device__ long long g_stamps[16384 * 8];
 #define FW_STAMP(k)
 #endif
 
-constexpr int FW_W = 8;          // waves per block
+constexpr int FW_W = 8;          // waves per block (deal8_begin deals the keys to eight)
 constexpr int FW_THREADS = 64 * FW_W;
 constexpr int FW_NJ = 4;         // keys per wave and pass (register tile columns)
 constexpr int FW_SS = 256;       // h per slice: four per lane
@@ -331,8 +331,8 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
     const T *kb = Kp + (size_t)b * Tk * H;
     KeyStream<T> ks;
     {
-        const int k_lo = (L * w) / FW_W;
-        ks.init(kb, v, H, lane, k_lo, (L * (w + 1)) / FW_W - k_lo, Hp / FW_SS);
+        const int k_lo = deal8_begin(L, w);
+        ks.init(kb, v, H, lane, k_lo, deal8_begin(L, w + 1) - k_lo, Hp / FW_SS);
     }
     ks.start();
 

@@ -30,6 +30,7 @@ constexpr int RC_W = 8;       // waves per block (== RC_RJ: wave jj finishes key
 constexpr int RC_THREADS = 64 * RC_W;
 static_assert(RC_RJ == kDsPad, "dS rows are padded to the key tile");
 static_assert(RC_W == RC_RJ, "one finishing wave per key of a tile");
+static_assert(RC_W == 8, "rows are dealt to eight waves");
 
 enum RcMode { RC_FACTOR = 0, RC_EXACT = 1, RC_STASH = 2 };
 
@@ -188,7 +189,7 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
         int pass = 0;
         for (int i_pass0 = 0; i_pass0 < Tq; i_pass0 += rows_per_pass, ++pass) {
             const int nrows = min(rows_per_pass, Tq - i_pass0);
-            const int r_lo = (nrows * w) / RC_W, r_hi = (nrows * (w + 1)) / RC_W;
+            const int r_lo = deal8_begin(nrows, w), r_hi = deal8_begin(nrows, w + 1);
             const int ni = r_hi - r_lo;              // 0..RC_RI
             const int i0 = i_pass0 + r_lo;
 
