@@ -43,8 +43,8 @@ TRAFFIC_FROM_PROFILE = {"cfg1_nmt_f32_B64_T50_H512": {"fwd_fused": 16.0e6 + 9.9e
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=500)
     ap.add_argument("--workload", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stash", action="store_true")
@@ -86,6 +86,11 @@ def main() -> int:
         db.fwd()
         db.bwd()
 
+    # ---- machine ceilings measured here, before the timed steps: a second or so of sustained arithmetic that
+    # also takes the device from its idle clocks to the ones it holds under load (a step is ~50 us; timed
+    # right after start-up, 200 of them read 5 % slower than in steady state)
+    cal = calibrate(eb, torch, dev)
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize(dev)
@@ -126,9 +131,6 @@ def main() -> int:
     eb.echo_attn_profile_enable(False)
     kernels = {k: {"launches": n, "avg_us": 1e3 * ms / n} for k, (n, ms) in prof.items()}
     dominant = max(kernels, key=lambda k: kernels[k]["avg_us"] * kernels[k]["launches"])
-
-    # ---- machine ceilings measured here
-    cal = calibrate(eb, torch, dev)
 
     def alu_roofline(name):
         us = kernels[name]["avg_us"]

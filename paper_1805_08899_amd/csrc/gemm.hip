@@ -254,13 +254,10 @@ __device__ __forceinline__ void dscore_block_dsplit(const float *__restrict__ dC
 #pragma unroll
         for (int u = 0; u < 2; ++u) pr[t][u] = P[((size_t)b * Tq + i) * Tk + min(lane + 64 * u, Tk - 1)];
     }
-    const int L = clamp_len(key_len[b], Tk);
     const float *dCrow = dC + ((size_t)b * Tq + min(i0 + lm, Tq - 1)) * Dv;
     const TV *Vb = V + (size_t)b * Tk * Dv;
     constexpr int U = 8;                          // 16-wide slices of d per wave and round
     const int rounds = (Dv + 64 * U - 1) / (64 * U);
-    const int n_jt = (L + 15) / 16;
-    const int items = n_jt * rounds;
     float4 a[U], bcur[U], bnxt[U];
     auto load_a = [&](int r) {
 #pragma unroll
@@ -276,10 +273,13 @@ __device__ __forceinline__ void dscore_block_dsplit(const float *__restrict__ dC
 #pragma unroll
         for (int u = 0; u < U; ++u) dst[u] = ld4(row, (size_t)min((4 * r + w) * 16 * U + 16 * u + 4 * lk, Dv - 4));
     };
-    if (items > 0) {
-        load_b(bcur, 0);
-        load_a(0);
-    }
+    // the first slices do not depend on the sample's key count (key tile 0 always exists in memory): they
+    // leave before key_len[b] has arrived
+    load_b(bcur, 0);
+    load_a(0);
+    const int L = clamp_len(key_len[b], Tk);
+    const int n_jt = (L + 15) / 16;
+    const int items = n_jt * rounds;
     f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
     for (int it = 0; it < items; ++it) {
         const int jt = it / rounds, r = it % rounds;
