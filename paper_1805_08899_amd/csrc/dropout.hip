@@ -54,7 +54,7 @@ __global__ __launch_bounds__(256) void k_dropout_fwd(const float *__restrict__ x
         const bool k2 = i + 2 < n && keep_from_word(r.z, p), k3 = i + 3 < n && keep_from_word(r.w, p);
         const float4 o = make_float4(k0 ? v.x * scale : 0.f, k1 ? v.y * scale : 0.f, k2 ? v.z * scale : 0.f,
                                      k3 ? v.w * scale : 0.f);
-        if (i + 3 < n) *reinterpret_cast<float4 *>(y + i) = o;
+        if (i + 3 < n) store4_streaming(y + i, o);
         else if (i < n) {
             y[i] = o.x;
             if (i + 1 < n) y[i + 1] = o.y;
@@ -77,9 +77,8 @@ __global__ __launch_bounds__(256) void k_dropout_bwd(const float *__restrict__ d
         const uint32_t bits = mask_bits[q / 8] >> (4 * (q & 7));        // the eight lanes of a group share the word
         if (i + 3 < n) {
             const float4 v = *reinterpret_cast<const float4 *>(dy + i);
-            *reinterpret_cast<float4 *>(dx + i) =
-                make_float4((bits & 1u) ? v.x * scale : 0.f, (bits & 2u) ? v.y * scale : 0.f,
-                            (bits & 4u) ? v.z * scale : 0.f, (bits & 8u) ? v.w * scale : 0.f);
+            store4_streaming(dx + i, make_float4((bits & 1u) ? v.x * scale : 0.f, (bits & 2u) ? v.y * scale : 0.f,
+                                                 (bits & 4u) ? v.z * scale : 0.f, (bits & 8u) ? v.w * scale : 0.f));
         } else {
             for (int c = 0; c < 3 && i + c < n; ++c) dx[i + c] = ((bits >> c) & 1u) ? dy[i + c] * scale : 0.f;
         }

@@ -419,7 +419,7 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
             for (int j = lane; j < max(Tk, Lp); j += 64) {
                 const float p = j < L ? srow[j] * inv : 0.f;
                 if (j < Lp) srow[j] = p;
-                if (j < Tk) Pb[(size_t)a * Tk + j] = p;
+                if (j < Tk) store_streaming(&Pb[(size_t)a * Tk + j], p);
             }
         } else {
             for (int j = lane; j < Lp; j += 64) srow[j] = 0.f;
@@ -466,7 +466,7 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
                 for (int t = 0; t < NR4; ++t)
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
-                        if (4 * t + r < ni) Cb[(size_t)(4 * t + r) * Dv + n] = acc[t][r];
+                        if (4 * t + r < ni) store_streaming(&Cb[(size_t)(4 * t + r) * Dv + n], acc[t][r]);
             }
 #pragma unroll
             for (int t = 0; t < NR4; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};

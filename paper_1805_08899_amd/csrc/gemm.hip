@@ -89,7 +89,7 @@ __device__ __forceinline__ void pv_block(const float *__restrict__ P, const TB *
                 o.z += old.z;
                 o.w += old.w;
             }
-            *dst = o;
+            store4_streaming(ob + (size_t)m * N + ncol, o);
         }
     }
 }
@@ -341,7 +341,7 @@ __device__ __forceinline__ void dscore_block_dsplit(const float *__restrict__ dC
             float *ds = dS + ((size_t)b * Tq + i) * pitch;
 #pragma unroll
             for (int u = 0; u < 2; ++u)
-                if (lane + 64 * u < pitch) ds[lane + 64 * u] = dsv[t][u];
+                if (lane + 64 * u < pitch) store_streaming(&ds[lane + 64 * u], dsv[t][u]);
             if (lane == 16 * t) ds_rowsum[(size_t)b * Tq + i] = t4;
         }
     }

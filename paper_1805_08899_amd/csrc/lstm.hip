@@ -30,14 +30,12 @@ template <> struct Vec<4> {
         const float4 t = *reinterpret_cast<const float4 *>(p);
         return Vec{{t.x, t.y, t.z, t.w}};
     }
-    __device__ __forceinline__ void store(float *p) const {
-        *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
-    }
+    __device__ __forceinline__ void store(float *p) const { store4_streaming(p, make_float4(v[0], v[1], v[2], v[3])); }
 };
 template <> struct Vec<1> {
     float v[1];
     __device__ __forceinline__ static Vec load(const float *p) { return Vec{{*p}}; }
-    __device__ __forceinline__ void store(float *p) const { *p = v[0]; }
+    __device__ __forceinline__ void store(float *p) const { store_streaming(p, v[0]); }
 };
 
 // STASH = false: writes h, c and the sum a.   STASH = true: writes h, c, the activations and tanh(c).

@@ -258,13 +258,14 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
                 if (j < L && hv) {
                     float *dst = dKb + (size_t)j * H + h;
                     const float val = v4 * tot;
-                    *dst = (pass == 0 && !acc) ? val : *dst + val;
+                    if (pass == 0 && !acc) store_streaming(dst, val);
+                    else *dst = *dst + val;
                 }
             }
             if (hv) {
 #pragma unroll
                 for (int a = 0; a < RC_RI; ++a)
-                    if (a < ni) dQb[(size_t)(i0 + a) * H + h] = v4 * accQ[a];
+                    if (a < ni) store_streaming(&dQb[(size_t)(i0 + a) * H + h], v4 * accQ[a]);
             }
             __syncthreads();   // the next pass restages buffer 0 and reuses s_part
         }
