@@ -50,7 +50,8 @@ __global__ __launch_bounds__(256) void k_cal_alu(float *__restrict__ out, int it
 
 __global__ __launch_bounds__(256) void k_cal_copy(const float4 *__restrict__ src, float4 *__restrict__ dst, size_t n4) {
     const size_t stride = (size_t)gridDim.x * 256;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) dst[i] = src[i];
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride)
+        store4_streaming(reinterpret_cast<float *>(dst + i), src[i]);
 }
 
 }  // namespace echo

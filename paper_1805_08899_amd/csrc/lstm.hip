@@ -27,7 +27,7 @@ template <int V> struct Vec;
 template <> struct Vec<4> {
     float v[4];
     __device__ __forceinline__ static Vec load(const float *p) {
-        const float4 t = *reinterpret_cast<const float4 *>(p);
+        const float4 t = load4_streaming(p);
         return Vec{{t.x, t.y, t.z, t.w}};
     }
     __device__ __forceinline__ void store(float *p) const { store4_streaming(p, make_float4(v[0], v[1], v[2], v[3])); }
