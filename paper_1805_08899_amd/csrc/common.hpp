@@ -28,16 +28,17 @@ __device__ __forceinline__ float4 ld4(const bf16_t *p, size_t i) {
     return r;
 }
 
-// Stores of results that this kernel does not read again go out as non-temporal (streaming) stores: they do not
-// stay behind as dirty lines for the end of the kernel to write back, which measured 0.3 to 0.6 us per kernel at
-// the smallest benchmark workload and 5 % of a pure streaming kernel.
 // Non-temporal loads, for inputs read once by the whole grid.  Measured: they help the LSTM block (nine input and
-// output streams at once, 180 -> 170 us) and hurt a single-stream copy (76 -> 93 us), so only the former uses them.
+// output streams at once, 180 -> 170 us) and hurt a single-stream copy (76 -> 93 us), so only the former uses them
+// (in the recompute kernel they cost 1 to 8 %).
 __device__ __forceinline__ float4 load4_streaming(const float *p) {
     typedef float f4 __attribute__((ext_vector_type(4)));
     const f4 v = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(p));
     return make_float4(v.x, v.y, v.z, v.w);
 }
+// Stores of results that this kernel does not read again go out as non-temporal (streaming) stores: they do not
+// stay behind as dirty lines for the end of the kernel to write back, which measured 0.3 to 0.6 us per kernel at
+// the smallest benchmark workload and 5 % of a pure streaming kernel.
 __device__ __forceinline__ void store_streaming(float *p, float x) { __builtin_nontemporal_store(x, p); }
 __device__ __forceinline__ void store4_streaming(float *p, float4 x) {
     typedef float f4 __attribute__((ext_vector_type(4)));

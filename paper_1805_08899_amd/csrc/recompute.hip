@@ -53,7 +53,7 @@ __device__ long long g_rc_stamps[16384 * 8];
 // ds_tile points at dS[b, i0, j0] (wave-uniform values, zero at masked keys);
 // t_tile at tmap[b, i0, 0, h] of this lane, kcol[c] = key index of column c
 // clamped into the valid range.
-template <int NI, int MODE>
+template <int NI, int MODE, int NJ>
 __device__ __forceinline__ void rc_tile(const float (&fq)[RC_RI], const float (&fk)[RC_RJ],
                                         const float *__restrict__ ds_tile, int pitch,
                                         const float *__restrict__ t_tile, size_t t_row, size_t t_key,
@@ -64,26 +64,26 @@ __device__ __forceinline__ void rc_tile(const float (&fq)[RC_RI], const float (&
 #pragma unroll
     for (int a = 0; a < NI; ++a) {
         const float4 d0 = *reinterpret_cast<const float4 *>(ds_tile + a * pitch);
-        const float4 d1 = *reinterpret_cast<const float4 *>(ds_tile + a * pitch + 4);
+        const float4 d1 = NJ > 4 ? *reinterpret_cast<const float4 *>(ds_tile + a * pitch + 4) : d0;
         const float d[RC_RJ] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
-        float r[RC_RJ], u[RC_RJ];
+        float r[NJ], u[NJ];
         if (MODE == RC_STASH) {
 #pragma unroll
-            for (int c = 0; c < RC_RJ; ++c) r[c] = __builtin_fmaf(-0.5f, t_tile[a * t_row + kcol[c] * t_key], 0.5f);
+            for (int c = 0; c < NJ; ++c) r[c] = __builtin_fmaf(-0.5f, t_tile[a * t_row + kcol[c] * t_key], 0.5f);
         } else {
 #pragma unroll
-            for (int c = 0; c < RC_RJ; ++c)
+            for (int c = 0; c < NJ; ++c)
                 r[c] = MODE == RC_FACTOR ? __builtin_fmaf(fq[a], fk[c], 1.0f) : fast_exp2(fq[a] + fk[c]) + 1.0f;
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int c = 0; c < RC_RJ; ++c) r[c] = fast_rcp(r[c]);
+            for (int c = 0; c < NJ; ++c) r[c] = fast_rcp(r[c]);
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
-        for (int c = 0; c < RC_RJ; ++c) u[c] = __builtin_fmaf(-r[c], r[c], r[c]);      // r (1 - r) = (1 - t^2) / 4
+        for (int c = 0; c < NJ; ++c) u[c] = __builtin_fmaf(-r[c], r[c], r[c]);      // r (1 - r) = (1 - t^2) / 4
         float q0 = 0.f, q1 = 0.f;
 #pragma unroll
-        for (int c = 0; c < RC_RJ; c += 2) {
+        for (int c = 0; c < NJ; c += 2) {
             accK[c] = __builtin_fmaf(d[c], u[c], accK[c]);
             q0 = __builtin_fmaf(d[c], u[c], q0);
             accV[c & 3] = __builtin_fmaf(d[c], r[c], accV[c & 3]);
@@ -97,13 +97,16 @@ __device__ __forceinline__ void rc_tile(const float (&fq)[RC_RI], const float (&
 }
 
 template <int MODE>
-__device__ __forceinline__ void rc_tile_n(int ni, const float (&fq)[RC_RI], const float (&fk)[RC_RJ],
+__device__ __forceinline__ void rc_tile_n(int ni, int live, const float (&fq)[RC_RI], const float (&fk)[RC_RJ],
                                           const float *__restrict__ ds_tile, int pitch,
                                           const float *__restrict__ t_tile, size_t t_row, size_t t_key,
                                           const int (&kcol)[RC_RJ],
                                           float (&accQ)[RC_RI], float (&accK)[RC_RJ], float (&accV)[4]) {
 #define RC_CASE(N) \
-    case N: rc_tile<N, MODE>(fq, fk, ds_tile, pitch, t_tile, t_row, t_key, kcol, accQ, accK, accV); break;
+    case N:                                                                                              \
+        if (live <= 4) rc_tile<N, MODE, 4>(fq, fk, ds_tile, pitch, t_tile, t_row, t_key, kcol, accQ, accK, accV); \
+        else rc_tile<N, MODE, RC_RJ>(fq, fk, ds_tile, pitch, t_tile, t_row, t_key, kcol, accQ, accK, accV);       \
+        break;
     switch (ni) {
         RC_CASE(1) RC_CASE(2) RC_CASE(3) RC_CASE(4) RC_CASE(5) RC_CASE(6) RC_CASE(7) RC_CASE(8)
         default: break;
@@ -217,6 +220,10 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
                 const int buf = jt & 1;
                 const int j0 = jt * RC_RJ;
                 const bool more = jt + 1 < n_jt;
+                // valid keys of this tile: a last tile with at most four evaluates half the columns (finer steps
+                // make the backward pass alone faster, but the code grows and forward + backward, which alternate
+                // in a training step, get slower)
+                const int live = L - j0;
                 if (more) fetch(jt + 1, i_pass0, nrows);
                 float accK[RC_RJ], fk[RC_RJ];
                 int kcol[RC_RJ];
@@ -230,7 +237,7 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
                     const float *t_tile = tmap + (((size_t)b * Tq + i0) * Tk) * H + hc;
 #pragma unroll
                     for (int c = 0; c < RC_RJ; ++c) fk[c] = 0.f;
-                    rc_tile_n<RC_STASH>(ni, fq, fk, ds_tile, RC_RJ, t_tile, (size_t)Tk * H, (size_t)H, kcol, accQ, accK,
+                    rc_tile_n<RC_STASH>(ni, live, fq, fk, ds_tile, RC_RJ, t_tile, (size_t)Tk * H, (size_t)H, kcol, accQ, accK,
                                         accV);
                 } else {
                     int kbig = 0;
@@ -239,11 +246,11 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
                     if (!(wave_qbig || kbig)) {
 #pragma unroll
                         for (int c = 0; c < RC_RJ; ++c) fk[c] = s_fk[buf][c][lane];
-                        rc_tile_n<RC_FACTOR>(ni, fq, fk, ds_tile, RC_RJ, nullptr, 0, 0, kcol, accQ, accK, accV);
+                        rc_tile_n<RC_FACTOR>(ni, live, fq, fk, ds_tile, RC_RJ, nullptr, 0, 0, kcol, accQ, accK, accV);
                     } else {
 #pragma unroll
                         for (int c = 0; c < RC_RJ; ++c) fk[c] = s_sk[buf][c][lane];
-                        rc_tile_n<RC_EXACT>(ni, sq, fk, ds_tile, RC_RJ, nullptr, 0, 0, kcol, accQ, accK, accV);
+                        rc_tile_n<RC_EXACT>(ni, live, sq, fk, ds_tile, RC_RJ, nullptr, 0, 0, kcol, accQ, accK, accV);
                     }
                 }
                 if (more) commit(jt + 1, buf ^ 1);
