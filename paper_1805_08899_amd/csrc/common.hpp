@@ -72,15 +72,28 @@ __device__ __forceinline__ float r_from_sum(float sq, float sk) {
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 __device__ __forceinline__ int wave_id() { return __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); }
 
+// Reductions over the 64 lanes, result in every lane.  Within a row of 16 lanes the partners are reached with DPP
+// (two quad permutations, then the two mirror patterns); the four row results are then read as scalars.  A dozen
+// full-rate instructions, where six general shuffles would each take a trip through the LDS crossbar.
+template <int CTRL> __device__ __forceinline__ float dpp_get(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float lane_value(float x, int l) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), l));
+}
 __device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
-    return x;
+    x += dpp_get<0xB1>(x);      // quad_perm [1,0,3,2]
+    x += dpp_get<0x4E>(x);      // quad_perm [2,3,0,1]
+    x += dpp_get<0x141>(x);     // row_half_mirror
+    x += dpp_get<0x140>(x);     // row_mirror
+    return (lane_value(x, 0) + lane_value(x, 16)) + (lane_value(x, 32) + lane_value(x, 48));
 }
 __device__ __forceinline__ float wave_max(float x) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
-    return x;
+    x = fmaxf(x, dpp_get<0xB1>(x));
+    x = fmaxf(x, dpp_get<0x4E>(x));
+    x = fmaxf(x, dpp_get<0x141>(x));
+    x = fmaxf(x, dpp_get<0x140>(x));
+    return fmaxf(fmaxf(lane_value(x, 0), lane_value(x, 16)), fmaxf(lane_value(x, 32), lane_value(x, 48)));
 }
 
 // ---------------------------------------------------------------------------
@@ -88,8 +101,8 @@ __device__ __forceinline__ float wave_max(float x) {
 // exchange per value instead of six.  At each level a lane keeps one half of
 // its values and hands the other half to the partner lane `OFF` away (levels
 // 32 and 16 with the gfx950 lane-swap instructions, 8 and 4 with DPP row
-// shifts selected by bank masks); once one value is left the remaining levels
-// are plain butterflies.  On return lane l holds in a[0] the full sum of value
+// shifts selected by bank masks, 2 and 1 with quad permutations); once one value is left the group of
+// lanes that shares it is summed with quad permutations and the two mirror patterns.  On return lane l holds in a[0] the full sum of value
 // number l / (64 / N).  N is a power of two <= 64; the order of additions is fixed.
 template <int CTRL, int BANK_MASK, bool BOUND>
 __device__ __forceinline__ float dpp_mov(float old, float src) {
@@ -111,11 +124,12 @@ __device__ __forceinline__ float transpose_pair(float x, float y, int lane) {
         const float t_lo = x + dpp_mov<SHL, 0xf, true>(0.f, x);  // x[l] + x[l + OFF]   (right where bit OFF is 0)
         const float t_hi = y + dpp_mov<SHR, 0xf, true>(0.f, y);  // y[l] + y[l - OFF]   (right where bit OFF is 1)
         return dpp_mov<0xE4, LO_BANKS, false>(t_hi, t_lo);       // identity move into the low banks only
-    } else {
+    } else {                                                     // partner inside the quad: one quad permutation
+        static_assert(OFF == 2 || OFF == 1, "lane offsets are powers of two below 64");
         const bool hi = (lane & OFF) != 0;
         const float keep = hi ? y : x;
         const float send = hi ? x : y;
-        return keep + __shfl_xor(send, OFF, 64);
+        return keep + dpp_get<OFF == 2 ? 0x4E : 0xB1>(send);
     }
 }
 
@@ -123,9 +137,12 @@ template <int N, int OFF>
 struct TransposeSumStep {
     template <int M>
     static __device__ __forceinline__ void run(float (&a)[M], int lane) {
-        if constexpr (N == 1) {      // one value left: plain butterfly over the remaining lane bits
-            a[0] += __shfl_xor(a[0], OFF, 64);
-            if constexpr (OFF > 1) TransposeSumStep<1, OFF / 2>::run(a, lane);
+        if constexpr (N == 1) {      // one value left: sum over the group of 2 OFF lanes that share it
+            static_assert(OFF <= 8, "a single value is left only inside a row");
+            a[0] += dpp_get<0xB1>(a[0]);                              // lanes l ^ 1
+            if constexpr (OFF >= 2) a[0] += dpp_get<0x4E>(a[0]);      // l ^ 2: the quad
+            if constexpr (OFF >= 4) a[0] += dpp_get<0x141>(a[0]);     // mirror in the half row: the other quad
+            if constexpr (OFF >= 8) a[0] += dpp_get<0x140>(a[0]);     // mirror in the row: the other half
         } else {
             constexpr int half = N / 2;
 #pragma unroll
