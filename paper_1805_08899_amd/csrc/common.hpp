@@ -78,6 +78,9 @@ __device__ __forceinline__ int wave_id() { return __builtin_amdgcn_readfirstlane
 template <int CTRL> __device__ __forceinline__ float dpp_get(float x) {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
 }
+template <int CTRL> __device__ __forceinline__ uint32_t dpp_get_u32(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, false);
+}
 __device__ __forceinline__ float lane_value(float x, int l) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), l));
 }

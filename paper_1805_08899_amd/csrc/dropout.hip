@@ -22,8 +22,9 @@ __device__ __forceinline__ u32x4 philox4x32_10(u32x4 c, uint32_t k0, uint32_t k1
             k0 += 0x9E3779B9u;
             k1 += 0xBB67AE85u;
         }
-        const uint32_t hi0 = __umulhi(0xD2511F53u, c.x), lo0 = 0xD2511F53u * c.x;
-        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c.z), lo1 = 0xCD9E8D57u * c.z;
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c.x, p1 = (uint64_t)0xCD9E8D57u * c.z;
+        const uint32_t hi0 = (uint32_t)(p0 >> 32), lo0 = (uint32_t)p0;
+        const uint32_t hi1 = (uint32_t)(p1 >> 32), lo1 = (uint32_t)p1;
         c = u32x4{hi1 ^ c.y ^ k0, lo1, hi0 ^ c.w ^ k1, lo0};
     }
     return c;
@@ -62,9 +63,9 @@ __global__ __launch_bounds__(256) void k_dropout_fwd(const float *__restrict__ x
         }
         // this lane's four bits at their place in the word of its group of eight lanes, then OR over the group
         uint32_t bits = ((uint32_t)k0 | (uint32_t)k1 << 1 | (uint32_t)k2 << 2 | (uint32_t)k3 << 3) << (4 * (lane & 7));
-        bits |= __shfl_xor(bits, 1, 64);
-        bits |= __shfl_xor(bits, 2, 64);
-        bits |= __shfl_xor(bits, 4, 64);
+        bits |= dpp_get_u32<0xB1>(bits);      // lanes l ^ 1 (quad permutation)
+        bits |= dpp_get_u32<0x4E>(bits);      // l ^ 2: the quad holds its 16 bits
+        bits |= dpp_get_u32<0x141>(bits);     // mirror in the half row: the other quad of the group of eight
         if ((lane & 7) == 0 && i < n) mask_bits[q / 8] = bits;
     }
 }
