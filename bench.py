@@ -37,7 +37,7 @@ SLOTS_CANONICAL = {"fwd_fused": 13.0, "recompute": 18.0}
 CAL_MIX = {"fwd_fused": "fwd_mix_tanh_per_s", "recompute": "bwd_mix_tanh_per_s"}
 # HBM bytes per launch (fetch + write) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the
 # same counters read for the library's plain copy kernel; source: profiles/bench_cfg1_kernels_and_counters.txt
-TRAFFIC_FROM_PROFILE = {"cfg1_nmt_f32_B64_T50_H512": {"fwd_fused": 16.0e6 + 9.9e6, "recompute": 16.2e6 + 13.2e6}}
+TRAFFIC_FROM_PROFILE = {"cfg1_nmt_f32_B64_T50_H512": {"fwd_fused": 16.0e6 + 10.0e6, "recompute": 16.2e6 + 13.2e6}}
 
 
 def main() -> int:
