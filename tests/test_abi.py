@@ -126,3 +126,20 @@ def test_lstm_cell_rejects_bad_arguments_without_launching():
     assert eb.echo_lstm_cell_bwd(4, 8, A, A + 8, A, A, A, A) == eb.ECHO_ERR_ALIGN
     assert eb.echo_lstm_cell_fwd_stash(4, 8, A, A, A, A, A, A, None) == eb.ECHO_ERR_NULL
     assert eb.echo_lstm_cell_bwd_stash(4, 8, A, A, A, None, A, A, A) == eb.ECHO_ERR_NULL
+
+
+def test_headers_are_plain_c():
+    """Every public header compiles on its own as C99 (no C++ or HIP types in the boundary)."""
+    import glob
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc here")
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    headers = sorted(glob.glob(os.path.join(inc, "*.h")))
+    assert len(headers) >= 3
+    for h in headers:
+        r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", "-"],
+                           input=f'#include "{h}"\n', text=True, capture_output=True)
+        assert r.returncode == 0, (h, r.stderr)
