@@ -293,9 +293,24 @@ def decoder_steps(eb, harness, torch, wl, inputs, dev, reps=20):
         torch.cuda.synchronize(dev)
         return (time.perf_counter() - t0) * 1e3 / reps, a.elapsed_time(b) / reps
 
+    dvp = torch.empty(wl.B, wl.H, **f32)
+
+    def sentence_one_launch_steps():
+        st = torch.cuda.current_stream(dev)
+        for t in (dK, dV, dvp):
+            t.zero_()
+        for t in range(T):
+            eb.check(eb.echo_attn_step_fwd(desc, q[t], full.Kp, full.V, full.v, full.key_len, ctx[t], P[t], stream=st))
+        for t in reversed(range(T)):
+            eb.check(eb.echo_attn_step_bwd(desc, dc[t], P[t], q[t], full.Kp, full.V, full.v, full.key_len, dQ[t], dK,
+                                           dV, dvp, stream=st))
+        eb.check(eb.echo_attn_step_finish(desc, dvp, dv, stream=st))
+
     for _ in range(3):
         sentence()
+        sentence_one_launch_steps()
     eager_wall, eager_gpu = timed(sentence)
+    fused_wall, fused_gpu = timed(sentence_one_launch_steps)
     side = torch.cuda.Stream(device=dev)
     side.wait_stream(torch.cuda.current_stream(dev))
     graph = torch.cuda.CUDAGraph()
@@ -305,7 +320,18 @@ def decoder_steps(eb, harness, torch, wl, inputs, dev, reps=20):
     torch.cuda.current_stream(dev).wait_stream(side)
     graph.replay()
     graph_wall, graph_gpu = timed(graph.replay)
+    side.wait_stream(torch.cuda.current_stream(dev))
+    graph1 = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph1, stream=side):
+            sentence_one_launch_steps()
+    torch.cuda.current_stream(dev).wait_stream(side)
+    graph1.replay()
+    fgraph_wall, fgraph_gpu = timed(graph1.replay)
     return {"steps": T, "launches_per_sentence": 4 * T + 3,
+            "one_launch_steps": {"launches_per_sentence": 2 * T + 4, "ms_per_sentence": fused_wall,
+                                 "gpu_ms_per_sentence": fused_gpu, "graph_gpu_ms_per_sentence": fgraph_gpu,
+                                 "graph_us_per_step_fwd_bwd": 1e3 * fgraph_gpu / T},
             "eager_ms_per_sentence": eager_wall, "eager_gpu_ms_per_sentence": eager_gpu,
             "graph_ms_per_sentence": graph_wall, "graph_gpu_ms_per_sentence": graph_gpu,
             "graph_us_per_step_fwd_bwd": 1e3 * graph_gpu / T}

@@ -114,6 +114,26 @@ echo_status_t echo_attn_bwd_accumulate(const echo_attn_desc_t *desc,
                                        float *dQp, float *dKp, float *dV, float *dv,
                                        void *workspace, size_t workspace_bytes, void *stream);
 
+/* The same decoder step in one launch per direction (Tq must be 1; Tk <= 8192; no workspace).
+ * echo_attn_step_fwd: same results as echo_attn_fwd with Tq = 1 (context [B,1,Dv] and P [B,1,Tk] overwritten).
+ * echo_attn_step_bwd: with one query per sample everything but dv
+ * is local to a sample, so one kernel takes each sample through dP, the softmax backward, the recomputation of
+ * tanh (Section 3.4) and dV; no workspace.  dQp [B,1,H] is overwritten; dKp [B,Tk,H], dV [B,Tk,Dv] and
+ * dv_part [B,H] (per-sample parts of dv) are ADDED TO: the caller clears them before the first step of a
+ * sentence.  After the last step echo_attn_step_finish adds the per-sample parts in index order:
+ * dv[h] = sum_b dv_part[b,h] (dv is overwritten).  Results equal echo_attn_bwd on the steps stacked along Tq up
+ * to the order of additions, and are reproducible for a given order of calls.
+ * Errors as echo_attn_bwd; ECHO_ERR_SHAPE also for Tq != 1 or Tk > 8192. */
+echo_status_t echo_attn_step_fwd(const echo_attn_desc_t *desc,
+                                 const void *Qp, const void *Kp, const void *V, const void *v,
+                                 const int32_t *key_len, float *context, float *P, void *stream);
+echo_status_t echo_attn_step_bwd(const echo_attn_desc_t *desc,
+                                 const float *dContext, const float *P,
+                                 const void *Qp, const void *Kp, const void *V, const void *v,
+                                 const int32_t *key_len,
+                                 float *dQp, float *dKp, float *dV, float *dv_part, void *stream);
+echo_status_t echo_attn_step_finish(const echo_attn_desc_t *desc, const float *dv_part, float *dv, void *stream);
+
 /* Comparison only: the baseline behaviour of Section 4.1, which stashes the
  * output of tanh as a feature map.  Same results as the pair above;
  * `tanh_map` is B*Tq*Tk*H fp32 (echo_attn_stash_bytes), written by the

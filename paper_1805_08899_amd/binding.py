@@ -39,6 +39,9 @@ EXPORTS = {
     "echo_attn_fwd": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 8 + [c_size_t, c_void_p]),
     "echo_attn_bwd": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 12 + [c_size_t, c_void_p]),
     "echo_attn_bwd_accumulate": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 12 + [c_size_t, c_void_p]),
+    "echo_attn_step_fwd": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 8),
+    "echo_attn_step_bwd": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 12),
+    "echo_attn_step_finish": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 3),
     "echo_attn_fwd_stash": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 9 + [c_size_t, c_void_p]),
     "echo_attn_bwd_stash": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 11 + [c_size_t, c_void_p]),
     "echo_attn_profile_enable": (None, [c_int]),
@@ -145,6 +148,20 @@ def echo_attn_bwd_accumulate(desc, dContext, P, Qp, Kp, V, v, key_len, dQp, dKp,
     return lib().echo_attn_bwd_accumulate(ctypes.byref(desc), _ptr(dContext), _ptr(P), _ptr(Qp), _ptr(Kp), _ptr(V),
                                           _ptr(v), _ptr(key_len), _ptr(dQp), _ptr(dKp), _ptr(dV), _ptr(dv),
                                           _ptr(workspace), _ws_bytes(workspace, workspace_bytes), _stream(stream))
+
+
+def echo_attn_step_fwd(desc, Qp, Kp, V, v, key_len, context, P, stream=None) -> int:
+    return lib().echo_attn_step_fwd(ctypes.byref(desc), _ptr(Qp), _ptr(Kp), _ptr(V), _ptr(v), _ptr(key_len),
+                                    _ptr(context), _ptr(P), _stream(stream))
+
+
+def echo_attn_step_bwd(desc, dContext, P, Qp, Kp, V, v, key_len, dQp, dKp, dV, dv_part, stream=None) -> int:
+    return lib().echo_attn_step_bwd(ctypes.byref(desc), _ptr(dContext), _ptr(P), _ptr(Qp), _ptr(Kp), _ptr(V), _ptr(v),
+                                    _ptr(key_len), _ptr(dQp), _ptr(dKp), _ptr(dV), _ptr(dv_part), _stream(stream))
+
+
+def echo_attn_step_finish(desc, dv_part, dv, stream=None) -> int:
+    return lib().echo_attn_step_finish(ctypes.byref(desc), _ptr(dv_part), _ptr(dv), _stream(stream))
 
 
 def echo_attn_fwd_stash(desc, Qp, Kp, V, v, key_len, context, P, tanh_map, workspace, workspace_bytes=None,

@@ -187,6 +187,49 @@ echo_status_t echo_attn_bwd_accumulate(const echo_attn_desc_t *desc, const float
                     workspace_bytes, stream);
 }
 
+echo_status_t echo_attn_step_fwd(const echo_attn_desc_t *desc, const void *Qp, const void *Kp, const void *V,
+                                 const void *v, const int32_t *key_len, float *context, float *P, void *stream) {
+    AttnShape s;
+    echo_status_t rc = check_desc(desc, &s);
+    if (rc != ECHO_OK) return rc;
+    if (s.Tq != 1 || echo::step_lds_bytes(s) > 64 * 1024) return ECHO_ERR_SHAPE;
+    if (!Qp || !Kp || !V || !v || !key_len || !context || !P) return ECHO_ERR_NULL;
+    const void *ptrs[] = {Qp, Kp, V, v, key_len, context, P};
+    for (const void *p : ptrs)
+        if (misaligned(p)) return ECHO_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ECHO_LAUNCH("step_fwd", echo::launch_step_fwd(s, Qp, Kp, V, v, key_len, context, P, st));
+    return ECHO_OK;
+}
+
+echo_status_t echo_attn_step_bwd(const echo_attn_desc_t *desc, const float *dContext, const float *P,
+                                 const void *Qp, const void *Kp, const void *V, const void *v,
+                                 const int32_t *key_len, float *dQp, float *dKp, float *dV, float *dv_part,
+                                 void *stream) {
+    AttnShape s;
+    echo_status_t rc = check_desc(desc, &s);
+    if (rc != ECHO_OK) return rc;
+    if (s.Tq != 1 || echo::step_lds_bytes(s) > 64 * 1024) return ECHO_ERR_SHAPE;
+    if (!dContext || !P || !Qp || !Kp || !V || !v || !key_len || !dQp || !dKp || !dV || !dv_part) return ECHO_ERR_NULL;
+    const void *ptrs[] = {dContext, P, Qp, Kp, V, v, key_len, dQp, dKp, dV, dv_part};
+    for (const void *p : ptrs)
+        if (misaligned(p)) return ECHO_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ECHO_LAUNCH("step_bwd", echo::launch_step_bwd(s, dContext, P, Qp, Kp, V, v, key_len, dQp, dKp, dV, dv_part, st));
+    return ECHO_OK;
+}
+
+echo_status_t echo_attn_step_finish(const echo_attn_desc_t *desc, const float *dv_part, float *dv, void *stream) {
+    AttnShape s;
+    echo_status_t rc = check_desc(desc, &s);
+    if (rc != ECHO_OK) return rc;
+    if (!dv_part || !dv) return ECHO_ERR_NULL;
+    if (misaligned(dv_part) || misaligned(dv)) return ECHO_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ECHO_LAUNCH("dv_reduce", echo::launch_dv_reduce(s, dv_part, dv, st));
+    return ECHO_OK;
+}
+
 echo_status_t echo_attn_fwd_stash(const echo_attn_desc_t *desc, const void *Qp, const void *Kp, const void *V,
                                   const void *v, const int32_t *key_len, float *context, float *P,
                                   float *tanh_map, void *workspace, size_t workspace_bytes, void *stream) {

@@ -43,5 +43,12 @@ hipError_t launch_recompute(const AttnShape &s, const void *Qp, const void *Kp, 
                             float *dv_part, hipStream_t st);
 // B4  dv[h] = sum_b dv_part[b,h], fixed order
 hipError_t launch_dv_reduce(const AttnShape &s, const float *dv_part, float *dv, hipStream_t st);
+// One decoder step (Tq = 1) of the backward pass in one launch; dKp, dV and dv_part [B,H] are added to.
+size_t step_lds_bytes(const AttnShape &s);
+hipError_t launch_step_fwd(const AttnShape &s, const void *Qp, const void *Kp, const void *V, const void *v,
+                           const int *key_len, float *C, float *P, hipStream_t st);
+hipError_t launch_step_bwd(const AttnShape &s, const float *dC, const float *P, const void *Qp, const void *Kp,
+                           const void *V, const void *v, const int *key_len, float *dQp, float *dKp, float *dV,
+                           float *dv_part, hipStream_t st);
 
 }  // namespace echo

@@ -143,3 +143,15 @@ def test_headers_are_plain_c():
         r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", "-"],
                            input=f'#include "{h}"\n', text=True, capture_output=True)
         assert r.returncode == 0, (h, r.stderr)
+
+
+def test_step_entry_points_validate():
+    one = eb.make_desc(4, 1, 7, 16, 16)
+    assert eb.echo_attn_step_bwd(one, A, A, A, A, A, A, A, A, A, A, None) == eb.ECHO_ERR_NULL
+    assert eb.echo_attn_step_bwd(one, A, A, A, A, A, A, A, A, A, A + 4, A) == eb.ECHO_ERR_ALIGN
+    assert eb.echo_attn_step_bwd(eb.make_desc(4, 2, 7, 16, 16), A, A, A, A, A, A, A, A, A, A, A) == eb.ECHO_ERR_SHAPE
+    assert eb.echo_attn_step_bwd(eb.make_desc(4, 1, 8193, 16, 16), A, A, A, A, A, A, A, A, A, A, A) == eb.ECHO_ERR_SHAPE
+    assert eb.echo_attn_step_fwd(one, A, A, A, A, A, A, None) == eb.ECHO_ERR_NULL
+    assert eb.echo_attn_step_fwd(eb.make_desc(4, 3, 7, 16, 16), A, A, A, A, A, A, A) == eb.ECHO_ERR_SHAPE
+    assert eb.echo_attn_step_finish(one, None, A) == eb.ECHO_ERR_NULL
+    assert eb.echo_attn_step_finish(one, A, A + 8) == eb.ECHO_ERR_ALIGN

@@ -136,6 +136,8 @@ STEP_CASES = [
     ("steps_tiny", 5, 6, 9, 64, 16, "f32"),
     ("steps_nmt_like", 16, 7, 50, 512, 512, "f32"),
     ("steps_bf16", 6, 4, 21, 128, 64, "bf16"),
+    ("steps_ragged_h_many_keys", 3, 3, 77, 70, 36, "f32"),
+    ("steps_h_not_multiple_of_4", 2, 2, 11, 33, 8, "f32"),
 ]
 
 
@@ -177,3 +179,23 @@ def test_decoder_steps_match_the_batched_layer(H, case):
            "dQp": torch.cat(dQ, dim=1).cpu().numpy(), "dKp": dK.cpu().numpy(), "dV": dV.cpu().numpy(),
            "dv": dv.cpu().numpy()}
     assert_parity(got, ref, inputs, dt, name)
+    # the same steps through the one-launch step kernel: per-sample parts of dv, summed once at the end
+    dQ1 = [torch.full((B, 1, Hh), float("nan"), **f32) for _ in range(T)]
+    dK1 = torch.zeros(B, Tk, Hh, **f32)
+    dV1 = torch.zeros(B, Tk, Dv, **f32)
+    dvp = torch.zeros(B, Hh, **f32)
+    dv1 = torch.full((Hh,), float("nan"), **f32)
+    ctx1 = [torch.full((B, 1, Dv), float("nan"), **f32) for _ in range(T)]
+    P1 = [torch.full((B, 1, Tk), float("nan"), **f32) for _ in range(T)]
+    for t in range(T):
+        eb.check(eb.echo_attn_step_fwd(step_desc, q_steps[t], full.Kp, full.V, full.v, full.key_len, ctx1[t], P1[t],
+                                       stream=st), "fused step fwd")
+    for t in reversed(range(T)):
+        eb.check(eb.echo_attn_step_bwd(step_desc, dc_steps[t], P1[t], q_steps[t], full.Kp, full.V, full.v,
+                                       full.key_len, dQ1[t], dK1, dV1, dvp, stream=st), "fused step bwd")
+    eb.check(eb.echo_attn_step_finish(step_desc, dvp, dv1, stream=st), "step finish")
+    torch.cuda.synchronize(full.device)
+    got1 = {"context": torch.cat(ctx1, dim=1).cpu().numpy(), "P": torch.cat(P1, dim=1).cpu().numpy(),
+            "dQp": torch.cat(dQ1, dim=1).cpu().numpy(), "dKp": dK1.cpu().numpy(), "dV": dV1.cpu().numpy(),
+            "dv": dv1.cpu().numpy()}
+    assert_parity(got1, ref, inputs, dt, name + " (one-launch steps)")
