@@ -10,7 +10,8 @@ from parity import assert_parity, oracle_outputs
 pytestmark = pytest.mark.gpu
 
 
-def test_decoder_steps_from_a_graph():
+@pytest.mark.parametrize("one_launch", [False, True], ids=["general_kernels", "step_kernels"])
+def test_decoder_steps_from_a_graph(one_launch):
     import torch
     assert torch.cuda.is_available(), "needs the GPU"
     from paper_1805_08899_amd import binding as eb, harness
@@ -30,8 +31,20 @@ def test_decoder_steps_from_a_graph():
     P = [torch.empty(B, 1, Tk, **f32) for _ in range(T)]
     dQ = [torch.empty(B, 1, Hh, **f32) for _ in range(T)]
     dK, dV, dv = torch.empty(B, Tk, Hh, **f32), torch.empty(B, Tk, Dv, **f32), torch.empty(Hh, **f32)
+    dvp = torch.empty(B, Hh, **f32)
 
-    def sentence():
+    def sentence_step_kernels():
+        st = torch.cuda.current_stream(dev)
+        for t in (dK, dV, dvp):
+            t.zero_()                                   # a fill kernel, not a memset node
+        for t in range(T):
+            eb.check(eb.echo_attn_step_fwd(desc, q[t], full.Kp, full.V, full.v, full.key_len, ctx[t], P[t], stream=st))
+        for t in reversed(range(T)):
+            eb.check(eb.echo_attn_step_bwd(desc, dc[t], P[t], q[t], full.Kp, full.V, full.v, full.key_len, dQ[t], dK,
+                                           dV, dvp, stream=st))
+        eb.check(eb.echo_attn_step_finish(desc, dvp, dv, stream=st))
+
+    def sentence_general():
         st = torch.cuda.current_stream(dev)
         for t in (dK, dV, dv):
             t.zero_()                                   # a fill kernel, not a memset node
@@ -41,6 +54,8 @@ def test_decoder_steps_from_a_graph():
             eb.check(eb.echo_attn_bwd_accumulate(desc, dc[t], P[t], q[t], full.Kp, full.V, full.v, full.key_len,
                                                  dQ[t], dK, dV, dv, ws, stream=st))
 
+    sentence = sentence_step_kernels if one_launch else sentence_general
+
     def snapshot():
         torch.cuda.synchronize(dev)
         return {"context": torch.cat(ctx, 1).cpu().numpy(), "P": torch.cat(P, 1).cpu().numpy(),
@@ -48,7 +63,7 @@ def test_decoder_steps_from_a_graph():
                 "dv": dv.cpu().numpy()}
 
     def poison():
-        for t in ctx + P + dQ + [dK, dV, dv]:
+        for t in ctx + P + dQ + [dK, dV, dv, dvp]:
             t.fill_(float("nan"))
 
     sentence()                                          # eager: also the warm-up before capture
