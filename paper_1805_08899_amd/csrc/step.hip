@@ -123,7 +123,7 @@ __global__ __launch_bounds__(ST_THREADS) void k_step_bwd(
                 const float g = ds * __builtin_fmaf(-rr, rr, rr);
                 accQ += g;
                 accR = __builtin_fmaf(ds, rr, accR);
-                if (hv) dKb[(size_t)(j0 + u) * H + h] = __builtin_fmaf(v4, g, oldk[u]);
+                if (hv) store_streaming(&dKb[(size_t)(j0 + u) * H + h], __builtin_fmaf(v4, g, oldk[u]));
             }
         }
         for (int c = c_lo + lane, m = 0; c < c_hi; c += 64, ++m) {
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(ST_THREADS) void k_step_bwd(
                 if (j0 + u < L) {
                     float *at = dVb + (size_t)(j0 + u) * Dv + c;
                     const float old = (n == 0 && m == 0) ? oldv0[u] : *at;
-                    *at = __builtin_fmaf(s_p[j0 + u], dc, old);
+                    store_streaming(at, __builtin_fmaf(s_p[j0 + u], dc, old));
                 }
             }
         }
