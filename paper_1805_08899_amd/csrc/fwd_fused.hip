@@ -513,12 +513,10 @@ static hipError_t launch_fwd_fused_t(const AttnShape &s, const void *Qp, const v
     const int Hp = (s.H + FW_SS - 1) / FW_SS * FW_SS;
     const int spitch = ((s.Tk + 3) & ~3) + 4;
     const size_t lds = fwd_lds_bytes(s, NG);
-    static size_t attr_bytes = 48 * 1024;   // dynamic LDS limit already granted to this instantiation
-    if (lds > attr_bytes) {
+    if (lds > 48 * 1024) {   // beyond the default dynamic LDS limit: raise it (no state is kept between calls)
         hipError_t e = hipFuncSetAttribute((const void *)k_fwd_fused<T, NG>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        attr_bytes = lds;
     }
     const int tiles = (s.Tq + RT - 1) / RT;
     const int samples_per_xcd = (s.B + FW_XCD - 1) / FW_XCD;
