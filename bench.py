@@ -122,6 +122,8 @@ def main() -> int:
 
     fwd_ms = time_only(db.fwd, args.steps)
     bwd_ms = time_only(db.bwd, args.steps)
+    # five more repeats of the same K steps, outside the timed region: their median shows how far one run moves
+    repeats = sorted(time_only(step, args.steps) for _ in range(5))
 
     # ---- per-kernel durations, HIP events on the launch stream
     eb.echo_attn_profile_enable(True)
@@ -206,6 +208,7 @@ def main() -> int:
         "config": {"workload": wl.name, "B": wl.B, "Tq": wl.Tq, "Tk": wl.Tk, "H": wl.H, "Dv": wl.Dv,
                    "in_dtype": wl.in_dtype, "mean_key_len": float(L.mean())},
         "ms_per_step_events": ms_per_step_events, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
+        "ms_per_step_repeats": {"median": repeats[2], "min": repeats[0], "max": repeats[4]},
         "kernels": kernels,
         "roofline": roofline,
         "hot_kernel_rooflines": hot_rooflines,
@@ -453,13 +456,17 @@ def cpu_baseline(wl, inputs):
     per_sample = wl.Tq * wl.Tk * wl.H
     nb = wl.B if per_sample * wl.B <= 2e8 else min(wl.B, cores)
     sl = slice(0, nb)
-    t0 = time.perf_counter()
-    parallel.forward_backward(inputs["Qp"][sl], inputs["Kp"][sl], inputs["V"][sl], inputs["v"],
-                              inputs["key_len"][sl], inputs["dContext"][sl], workers=cores)
-    dt = time.perf_counter() - t0
+    reps = 3 if per_sample * nb <= 2e8 else 1      # the small workloads are repeated: the first run pays for start-up
+    dt = None
+    for _ in range(reps):
+        t0 = time.perf_counter()
+        parallel.forward_backward(inputs["Qp"][sl], inputs["Kp"][sl], inputs["V"][sl], inputs["v"],
+                                  inputs["key_len"][sl], inputs["dContext"][sl], workers=cores)
+        d = time.perf_counter() - t0
+        dt = d if dt is None else min(dt, d)
     frac = float(np.clip(inputs["key_len"][sl], 0, wl.Tk).sum() / np.clip(inputs["key_len"], 0, wl.Tk).sum())
     return {"value": frac / dt, "unit": "calls/s", "cores": min(cores, nb), "kind": "oracle",
-            "sample": f"{nb} of {wl.B} samples of {wl.name}, one fwd+bwd in float64, {dt:.2f} s wall; "
+            "sample": f"{nb} of {wl.B} samples of {wl.name}, one fwd+bwd in float64, best of {reps}: {dt:.2f} s wall; "
                       f"scaled to a whole call by the share of unmasked keys ({frac:.3f})"}
 
 
