@@ -56,8 +56,8 @@ def main() -> int:
                     help="also time the per-step decoder form of the same workload (Tq calls with one query each)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (a batch shards over samples, "
-              "see DESIGN.md, but no multi-GPU path is built)", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (a batch would shard over its samples with "
+              "one small all-reduce for dv, but no multi-GPU path is built)", file=sys.stderr)
         return 2
 
     import numpy as np
