@@ -79,7 +79,7 @@ struct KeyStream {
         v = v_;
         H = H_;
         lane4 = 4 * lane;
-        k_lo = k_lo_;
+        k_lo = nk > 0 ? k_lo_ : 0;        // a wave without keys loads key 0 (its own first key may be row L)
         NS = NS_;
         npass = (nk + FW_NJ - 1) / FW_NJ;
         const int np = max(npass, 1);

@@ -66,6 +66,10 @@ EDGE = [
     ("wide_values_short_keys", 2, 20, 40, 64, 1040, "f32", None),
     ("keys_just_past_the_short_path", 2, 18, 129, 64, 24, "f32", None),
     ("fused_forward_h_not_multiple_of_256", 3, 11, 13, 300, 12, "f32", None),
+    # fused forward with fewer keys than waves and every key valid: the waves without keys must stay inside Kp
+    ("fused_forward_one_key", 3, 5, 1, 32, 4, "f32", [1, 1, 1]),
+    ("fused_forward_two_keys", 2, 9, 2, 64, 8, "f32", [2, 2]),
+    ("fused_forward_three_keys", 2, 9, 3, 260, 8, "f32", [3, 3]),
 ]
 
 
