@@ -101,6 +101,25 @@ echo_status_t echo_attn_bwd(const echo_attn_desc_t *desc,
                             float *dQp, float *dKp, float *dV, float *dv,
                             void *workspace, size_t workspace_bytes, void *stream);
 
+/* For callers that cannot allocate device memory or hand over a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): echo_attn_bwd with the workspace taken from a buffer of
+ * ECHO_ATTN_STATIC_SCRATCH_BYTES that is part of the library's device image (every GPU the library runs on holds
+ * one until the process ends).  Same arguments, kernels and results as echo_attn_bwd; calls no allocator.
+ *   - The device that `stream` belongs to must be the current device of the calling thread.  The first call on
+ *     a device looks up the address of that device's buffer (no allocation); later calls reuse it.
+ *   - ECHO_ERR_WORKSPACE if echo_attn_bwd_workspace_bytes(desc) exceeds ECHO_ATTN_STATIC_SCRATCH_BYTES
+ *     (echo_last_error_detail() then names both sizes); nothing is launched.
+ *   - All calls on one GPU share that GPU's buffer, which keeps the last call's contents (nothing in it has to
+ *     be cleared between calls): two calls that may overlap on one GPU (different streams without an event
+ *     between them, several host threads) race, and so does a graph replayed concurrently with itself. */
+#define ECHO_ATTN_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+echo_status_t echo_attn_bwd_static(const echo_attn_desc_t *desc,
+                                   const float *dContext, const float *P,
+                                   const void *Qp, const void *Kp, const void *V, const void *v,
+                                   const int32_t *key_len,
+                                   float *dQp, float *dKp, float *dV, float *dv,
+                                   void *stream);
+
 /* Backward of one decoder step (Section 2: the decoder produces one query at a time against the same encoder
  * states, so Kp, V and v are shared by all steps of a sentence and their gradients are sums over the steps).
  * Same as echo_attn_bwd, except that dKp, dV and dv are ADDED TO instead of overwritten: the caller clears them
@@ -178,7 +197,8 @@ echo_status_t echo_attn_calibrate(int kind, int blocks, int iters, const void *s
                                   double *work, void *stream);
 
 const char *echo_status_string(echo_status_t s);
-/* Kernel name and HIP error text of the calling thread's last ECHO_ERR_HIP ("" if none). */
+/* Kernel name and HIP error text of the calling thread's last ECHO_ERR_HIP, or the two sizes of
+ * echo_attn_bwd_static's last ECHO_ERR_WORKSPACE ("" if none). */
 const char *echo_last_error_detail(void);
 const char *echo_version(void);
 

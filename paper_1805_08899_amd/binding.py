@@ -38,6 +38,7 @@ EXPORTS = {
     "echo_attn_stash_bytes": (c_size_t, [POINTER(echo_attn_desc_t)]),
     "echo_attn_fwd": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 8 + [c_size_t, c_void_p]),
     "echo_attn_bwd": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 12 + [c_size_t, c_void_p]),
+    "echo_attn_bwd_static": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 12),
     "echo_attn_bwd_accumulate": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 12 + [c_size_t, c_void_p]),
     "echo_attn_step_fwd": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 8),
     "echo_attn_step_bwd": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 12),
@@ -141,6 +142,15 @@ def echo_attn_bwd(desc, dContext, P, Qp, Kp, V, v, key_len, dQp, dKp, dV, dv, wo
     return lib().echo_attn_bwd(ctypes.byref(desc), _ptr(dContext), _ptr(P), _ptr(Qp), _ptr(Kp), _ptr(V), _ptr(v),
                                _ptr(key_len), _ptr(dQp), _ptr(dKp), _ptr(dV), _ptr(dv), _ptr(workspace),
                                _ws_bytes(workspace, workspace_bytes), _stream(stream))
+
+
+ECHO_ATTN_STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def echo_attn_bwd_static(desc, dContext, P, Qp, Kp, V, v, key_len, dQp, dKp, dV, dv, stream=None) -> int:
+    return lib().echo_attn_bwd_static(ctypes.byref(desc), _ptr(dContext), _ptr(P), _ptr(Qp), _ptr(Kp), _ptr(V),
+                                      _ptr(v), _ptr(key_len), _ptr(dQp), _ptr(dKp), _ptr(dV), _ptr(dv),
+                                      _stream(stream))
 
 
 def echo_attn_bwd_accumulate(desc, dContext, P, Qp, Kp, V, v, key_len, dQp, dKp, dV, dv, workspace,

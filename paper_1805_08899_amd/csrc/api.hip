@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -145,6 +146,37 @@ echo_status_t bwd_impl(const echo_attn_desc_t *desc, const float *dContext, cons
     return ECHO_OK;
 }
 
+// ---- device memory that belongs to the library: the backward workspace of echo_attn_bwd_static -------------
+// In host code `scratch` is only the handle of the symbol, not an address on the device; the address of each
+// device's copy is looked up once per device (with that device current) and kept in g_scratch_ptr.
+constexpr size_t kStaticScratchBytes = ECHO_ATTN_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+echo_status_t static_scratch(void **out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        g_last_error = std::string("static scratch: hipGetDevice: ") + hipGetErrorString(e);
+        return ECHO_ERR_HIP;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            g_last_error = std::string("static scratch: hipGetSymbolAddress: ") + hipGetErrorString(e);
+            return ECHO_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return ECHO_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -177,6 +209,25 @@ echo_status_t echo_attn_bwd(const echo_attn_desc_t *desc, const float *dContext,
                             void *stream) {
     return bwd_impl(desc, dContext, P, nullptr, false, false, Qp, Kp, V, v, key_len, dQp, dKp, dV, dv, workspace,
                     workspace_bytes, stream);
+}
+
+echo_status_t echo_attn_bwd_static(const echo_attn_desc_t *desc, const float *dContext, const float *P,
+                                   const void *Qp, const void *Kp, const void *V, const void *v,
+                                   const int32_t *key_len, float *dQp, float *dKp, float *dV, float *dv,
+                                   void *stream) {
+    AttnShape s;
+    echo_status_t rc = check_desc(desc, &s);
+    if (rc != ECHO_OK) return rc;
+    if (bwd_layout(s).total > kStaticScratchBytes) {
+        g_last_error = "echo_attn_bwd_static: this shape needs " + std::to_string(bwd_layout(s).total) +
+                       " bytes of workspace, the library's own buffer holds " + std::to_string(kStaticScratchBytes);
+        return ECHO_ERR_WORKSPACE;
+    }
+    void *ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc != ECHO_OK) return rc;
+    return bwd_impl(desc, dContext, P, nullptr, false, false, Qp, Kp, V, v, key_len, dQp, dKp, dV, dv, ws,
+                    kStaticScratchBytes, stream);
 }
 
 echo_status_t echo_attn_bwd_accumulate(const echo_attn_desc_t *desc, const float *dContext, const float *P,
