@@ -105,7 +105,8 @@ __device__ __forceinline__ float wave_max(float x) {
 // its values and hands the other half to the partner lane `OFF` away (levels
 // 32 and 16 with the gfx950 lane-swap instructions, 8 and 4 with DPP row
 // shifts selected by bank masks, 2 and 1 with quad permutations); once one value is left the group of
-// lanes that shares it is summed with quad permutations and the two mirror patterns.  On return lane l holds in a[0] the full sum of value
+// lanes that shares it is summed with quad permutations and the two mirror patterns (and, for N < 8, lane swaps
+// of a value with itself).  On return lane l holds in a[0] the full sum of value
 // number l / (64 / N).  N is a power of two <= 64; the order of additions is fixed.
 template <int CTRL, int BANK_MASK, bool BOUND>
 __device__ __forceinline__ float dpp_mov(float old, float src) {
@@ -141,11 +142,12 @@ struct TransposeSumStep {
     template <int M>
     static __device__ __forceinline__ void run(float (&a)[M], int lane) {
         if constexpr (N == 1) {      // one value left: sum over the group of 2 OFF lanes that share it
-            static_assert(OFF <= 8, "a single value is left only inside a row");
             a[0] += dpp_get<0xB1>(a[0]);                              // lanes l ^ 1
             if constexpr (OFF >= 2) a[0] += dpp_get<0x4E>(a[0]);      // l ^ 2: the quad
             if constexpr (OFF >= 4) a[0] += dpp_get<0x141>(a[0]);     // mirror in the half row: the other quad
             if constexpr (OFF >= 8) a[0] += dpp_get<0x140>(a[0]);     // mirror in the row: the other half
+            if constexpr (OFF >= 16) a[0] = transpose_pair<16>(a[0], a[0], lane);   // the neighbouring row
+            if constexpr (OFF >= 32) a[0] = transpose_pair<32>(a[0], a[0], lane);   // the other half of the wave
         } else {
             constexpr int half = N / 2;
 #pragma unroll

@@ -4,17 +4,19 @@
 // one fused kernel instead of many small ones, fewer launches and accesses).
 //
 // Block = (sample b, up to RT = 8 NG query rows), 8 waves.
-//   A  exp(2q) of the rows goes to LDS (taken once per block).
+//   A  exp(2q) / v of the rows and 1 / v go to LDS (taken once per block).
 //   B  the valid keys are dealt to the waves in eight contiguous shares that differ by at most one key;
 //      a wave walks its share in passes of up to four keys.  A lane owns four
 //      consecutive h of every 256-wide slice, so a key row arrives as one
 //      16-byte load per lane (every K element is exponentiated once per block)
-//      and a staged query row as one 16-byte LDS read.  Per row, key and h
-//          acc += v[h] * rcp(fma(exp(2q), exp(2k), 1))
-//      and a pass finishes with one transposing wave reduction of its
-//      rows x keys tile.  A pass that met a pre-activation beyond the
-//      factorisation limit is redone by a small exact routine that
-//      exponentiates the sum.
+//      and a staged query row as one 16-byte LDS read.
+//      With r = 1 / (exp(2(q+k)) + 1), tanh = 1 - 2r, the score is sum_h v - 2 sum_h v r, and the first
+//      term drops out of the softmax.  v r = 1 / a with a = 1/v + (exp(2q)/v) exp(2k): one multiply-add.
+//      Two neighbouring h share one reciprocal: 1/a0 + 1/a1 = (a0 + a1) / (a0 a1), so per row, key and
+//      pair of h the loop issues 2 fma, 1 add, 1 mul, 1 rcp, 1 fma.
+//      A pass finishes with one transposing wave reduction of its rows x keys tile.  A pass whose
+//      operands could leave the range in which a0 a1 stays finite is redone by a small exact routine
+//      that exponentiates the sum.
 //   C  the waves normalise the rows (softmax over the valid keys) and write P.
 //   D  context = P V on the matrix cores: v_mfma_f32_4x4x1 treats the 64 lanes
 //      as 16 column groups of 4, so a lane owns one output column and reads V
@@ -41,10 +43,10 @@ namespace echo {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 #ifdef ECHO_TIMING   // development aid: per-block phase time stamps (100 MHz counter), read back with echo_debug_stamps
-__device__ long long g_stamps[16384 * 8];
-#define FW_STAMP(k)                                                                                 \
-    do {                                                                                            \
-        if (threadIdx.x == 0 && blockIdx.x < 16384) g_stamps[blockIdx.x * 8 + (k)] = wall_clock64(); \
+__device__ long long g_stamps[16384 * 16];
+#define FW_STAMP(k)                                                                                  \
+    do {                                                                                             \
+        if (threadIdx.x == 0 && blockIdx.x < 16384) g_stamps[blockIdx.x * 16 + (k)] = wall_clock64(); \
     } while (0)
 #else
 #define FW_STAMP(k)
@@ -58,8 +60,56 @@ constexpr int FW_XCD = 8;        // blockIdx.x mod 8 selects the XCD
 constexpr int FW_CU_PER_XCD = 32;
 constexpr int FW_KB = 16;        // value rows per batch in the context phase (two batches in flight per wave)
 constexpr int FW_MAX_RANKED_B = 128;   // the in-kernel ranking keeps two lengths per lane
+constexpr int FW_ROW_REGS = 16;  // row mode: 16-byte registers a wave spends on its keys (keys x slices)
+
+// row mode: the longest key share a wave can hold with ns slices of h (1 stands in for streaming mode, ns = 0)
+constexpr int fw_row_max_keys(int ns) { return ns <= 0 ? 1 : (FW_ROW_REGS / ns > 8 ? 8 : FW_ROW_REGS / ns); }
 
 __device__ __forceinline__ float comp(const float4 &x, int c) { return c == 0 ? x.x : c == 1 ? x.y : c == 2 ? x.z : x.w; }
+
+// Barrier for data exchanged through LDS only: waits for this wave's LDS operations, not for its global
+// loads and stores (__syncthreads() would also wait for every prefetch in flight).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Pairs of reciprocals share one division (see B at the top): the product a0 a1 must stay finite.
+// |a| <= max|1/v| + max|exp(2q)/v| max exp(2k); a pass is evaluated by the factor path only while this
+// bound is below kPairLimit = sqrt(FLT_MAX) (with a little room).  An entry of v below kTinyV in magnitude
+// is taken as zero (it changes a score by less than 1e-18): its 1/v is replaced by kHugeC and its
+// exp(2q)/v by 0, so that the pair still evaluates to the other entry's term.
+constexpr float kPairLimit = 1.8e19f;
+constexpr float kTinyV = 1e-18f;
+constexpr float kHugeC = 1e18f;
+
+// One row of the tile against NJ keys for the four h of a lane: t = 1/v + (exp(2q)/v) exp(2k), then per pair
+// of h one sum, one product, one reciprocal and one multiply-add into acc.  The evaluations are issued in
+// batches so that no instruction waits for the one before it.  fk[q][c]: exp(2k) of key c at the lane's q-th h.
+template <int NJ>
+__device__ __forceinline__ void fw_row_keys(const float4 &fq, const float4 &cv, const float (&fk)[4][NJ], float (&acc)[NJ]) {
+    float t[4][NJ], sm[2][NJ], pr[2][NJ];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int c = 0; c < NJ; ++c) t[q][c] = __builtin_fmaf(comp(fq, q), fk[q][c], comp(cv, q));
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+        for (int c = 0; c < NJ; ++c) {
+            sm[h2][c] = t[2 * h2][c] + t[2 * h2 + 1][c];
+            pr[h2][c] = t[2 * h2][c] * t[2 * h2 + 1][c];
+        }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+        for (int c = 0; c < NJ; ++c) pr[h2][c] = fast_rcp(pr[h2][c]);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+        for (int c = 0; c < NJ; ++c) acc[c] = __builtin_fmaf(sm[h2][c], pr[h2][c], acc[c]);
+    __builtin_amdgcn_sched_barrier(0);
+}
 
 // The keys of one wave as a stream of slices: pass p covers keys j0(p) .. j0(p+1), slice s the columns
 // 256 s + 4 lane .. + 3.  `cur` is the slice about to be consumed; once its values have been used advance()
@@ -67,16 +117,14 @@ __device__ __forceinline__ float comp(const float4 &x, int c) { return c == 0 ? 
 // use.  Rows past a pass's last key repeat it.
 template <typename T>
 struct KeyStream {
-    const T *kb, *v;
+    const T *kb;
     int H, lane4, k_lo, npass, NS;
     int base, extra;                    // pass p has base + (p < extra) keys
     int p_f, s_f;                       // slice that the next fetch will load
-    float4 cur[FW_NJ], vcur;
-    bool von;
+    float4 cur[FW_NJ];
 
-    __device__ __forceinline__ void init(const T *kb_, const T *v_, int H_, int lane, int k_lo_, int nk, int NS_) {
+    __device__ __forceinline__ void init(const T *kb_, int H_, int lane, int k_lo_, int nk, int NS_) {
         kb = kb_;
-        v = v_;
         H = H_;
         lane4 = 4 * lane;
         k_lo = nk > 0 ? k_lo_ : 0;        // a wave without keys loads key 0 (its own first key may be row L)
@@ -96,17 +144,14 @@ struct KeyStream {
     __device__ __forceinline__ void fetch() {
         const int pc = min(p_f, max(npass, 1) - 1);
         const int j0 = pass_begin(pc), j1 = max(pass_begin(pc + 1), j0 + 1);
-        const int h = s_f * FW_SS + lane4;
-        // columns past H: the load repeats the row's last four values (finite or caught by the limit
-        // check), exp(2q) is 0 there and v reads as 0, so they add nothing
-        const int hc = min(h, H - 4);
+        // columns past H: the load repeats the row's last four values; exp(2q)/v is 0 and 1/v is kHugeC
+        // there, so they add nothing
+        const int hc = min(s_f * FW_SS + lane4, H - 4);
 #pragma unroll
         for (int c = 0; c < FW_NJ; ++c) {
             const int j = min(j0 + c, j1 - 1);
             cur[c] = ld4(kb, (size_t)(unsigned)(j * H + hc));
         }
-        vcur = ld4(v, (size_t)(unsigned)hc);     // masked by the consumer: von tells whether the columns exist
-        von = h < H;
         const bool wrap = s_f + 1 == NS;
         s_f = wrap ? 0 : s_f + 1;
         p_f = wrap ? min(p_f + 1, npass) : p_f;
@@ -115,15 +160,16 @@ struct KeyStream {
     __device__ __forceinline__ void advance() { fetch(); }
 };
 
-// One pass of one wave: NJ keys starting at column jcol0 of the score tile, all rows of the block, all slices
-// of h, factor path only.  s_e: LDS rows of exp(2q), pitch Hp.  NI > 0: exactly NI rows are live, known at
-// compile time (no per-row branches, the next row's LDS read is issued a row ahead); NI == 0: the first ni.
-// The evaluations of a row are issued in batches (multiply-adds, reciprocals, accumulations) so that no
-// instruction waits for the one before it.  Returns true if a key value was beyond the factor limit, in which case nothing was written
-// and the caller must redo the pass exactly.
+// Streaming mode, one pass of one wave: NJ keys starting at column jcol0 of the score tile, all rows of the
+// block, all slices of h, factor path only.  s_e: LDS rows of exp(2q)/v, pitch Hp; s_c: 1/v.  NI > 0: exactly
+// NI rows are live, known at compile time (no per-row branches, the next row's LDS read is issued a row ahead);
+// NI == 0: the first ni.  What is written is the score without its key-independent term: -2 sum_h v r.
+// qe_max, c_max: the block's largest |exp(2q)/v| and |1/v|.  Returns true if the operands may leave the
+// range of the factor path, in which case nothing was written and the caller must redo the pass exactly.
 template <typename T, int NG, int NJ, int NI>
-__device__ __forceinline__ bool fw_pass(const float *__restrict__ s_e, int Hp, int ni, KeyStream<T> &ks,
-                                        float *__restrict__ s_S, int spitch, int jcol0) {
+__device__ __forceinline__ bool fw_pass(const float *__restrict__ s_e, const float *__restrict__ s_c, int Hp, int ni,
+                                        KeyStream<T> &ks, float qe_max, float c_max, float *__restrict__ s_S,
+                                        int spitch, int jcol0) {
     constexpr int RT = 8 * NG;
     constexpr bool FULL = NI > 0;
     constexpr int NR = FULL ? NI : RT;       // rows the unrolled loops visit
@@ -133,25 +179,18 @@ __device__ __forceinline__ bool fw_pass(const float *__restrict__ s_e, int Hp, i
     for (int a = 0; a < RT; ++a)
 #pragma unroll
         for (int c = 0; c < NJ; ++c) acc[a][c] = 0.f;
-    float vsum = 0.f, kmax = 0.f;
+    float kmax = 0.f;                        // largest exp(2k) this lane met
 
     for (int s = 0; s < ks.NS; ++s) {
-        float fk[4][NJ], vv[4];
+        float fk[4][NJ];
 #pragma unroll
         for (int c = 0; c < NJ; ++c) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float x = comp(ks.cur[c], q);
-                kmax = fmaxf(kmax, fabsf(x));
-                fk[q][c] = fast_exp2(kTwoLog2e * x);
-            }
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            vv[q] = ks.von ? comp(ks.vcur, q) : 0.f;
-            vsum += vv[q];
+            for (int q = 0; q < 4; ++q) fk[q][c] = fast_exp2(kTwoLog2e * comp(ks.cur[c], q));
+            kmax = fmaxf(fmaxf(kmax, fk[0][c]), fmaxf(fk[1][c], fmaxf(fk[2][c], fk[3][c])));
         }
         ks.advance();
+        const float4 cv = *reinterpret_cast<const float4 *>(s_c + s * FW_SS + 4 * lane);
         const float *e_col = s_e + s * FW_SS + 4 * lane;
         float4 fq_next = *reinterpret_cast<const float4 *>(e_col);
 #pragma unroll
@@ -164,50 +203,32 @@ __device__ __forceinline__ bool fw_pass(const float *__restrict__ s_e, int Hp, i
                 } else {
                     fq = *reinterpret_cast<const float4 *>(e_col + a * Hp);
                 }
-                // two batches of 2 NJ evaluations each: multiply-adds, reciprocals, accumulations
-#pragma unroll
-                for (int q0 = 0; q0 < 4; q0 += 2) {
-                    float t[2][NJ];
-#pragma unroll
-                    for (int q = 0; q < 2; ++q)
-#pragma unroll
-                        for (int c = 0; c < NJ; ++c) t[q][c] = __builtin_fmaf(comp(fq, q0 + q), fk[q0 + q][c], 1.0f);
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int q = 0; q < 2; ++q)
-#pragma unroll
-                        for (int c = 0; c < NJ; ++c) t[q][c] = fast_rcp(t[q][c]);
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int q = 0; q < 2; ++q)
-#pragma unroll
-                        for (int c = 0; c < NJ; ++c) acc[a][c] = __builtin_fmaf(vv[q0 + q], t[q][c], acc[a][c]);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
+                fw_row_keys<NJ>(fq, cv, fk, acc[a]);
             }
         }
     }
-    if (__any(kmax > kFactorLimit)) return true;
-    // S = sum_h v (1 - 2r): per lane first, then one transposing reduction for the whole tile
+    // the negation also sends a NaN bound (NaN or infinite operands) to the exact path
+    if (__any(!(__builtin_fmaf(qe_max, kmax, c_max) < kPairLimit))) return true;
+    // per lane first, then one transposing reduction for the whole tile
     constexpr int NP = RT * NJ;
     constexpr int NPOW = NP <= 8 ? 8 : NP <= 16 ? 16 : NP <= 32 ? 32 : 64;
     float flat[NPOW];
 #pragma unroll
     for (int p = 0; p < NPOW; ++p) {
         const int a = p / NJ, c = p % NJ;
-        flat[p] = p < NP ? __builtin_fmaf(-2.f, acc[a < RT ? a : 0][c], vsum) : 0.f;
+        flat[p] = p < NP ? acc[a < RT ? a : 0][c] : 0.f;
     }
     const float tot = wave_transpose_sum<NPOW>(flat);
     const int p = lane / (64 / NPOW);
     if ((lane % (64 / NPOW)) == 0 && p < NP) {
         const int a = p / NJ, c = p % NJ;
-        if (a < ni) s_S[a * spitch + jcol0 + c] = tot;
+        if (a < ni) s_S[a * spitch + jcol0 + c] = -2.f * tot;
     }
     return false;
 }
 
-// The same tile with tanh taken from the exponential of the sum: correct for any finite input.
-// Straightforward loops; only reached for pre-activations beyond the factor limit.
+// The same tile with r taken from the exponential of the sum: correct for any finite input.
+// Straightforward loops; only reached for operands beyond the range of the factor path.
 template <typename T>
 __device__ __noinline__ void fw_pass_exact(const T *__restrict__ qrow0, int ni, const T *__restrict__ krow0, int nj,
                                            int H, const T *__restrict__ v, float *__restrict__ s_S, int spitch,
@@ -219,13 +240,105 @@ __device__ __noinline__ void fw_pass_exact(const T *__restrict__ qrow0, int ni, 
             for (int h = lane; h < H; h += 64) {
                 const float sq = kTwoLog2e * ld(qrow0, (size_t)a * H + h);
                 const float sk = kTwoLog2e * ld(krow0, (size_t)c * H + h);
-                const float vh = ld(v, h);
-                acc += vh * __builtin_fmaf(-2.f, r_from_sum(sq, sk), 1.f);
+                acc = __builtin_fmaf(ld(v, h), r_from_sum(sq, sk), acc);
             }
             acc = wave_sum(acc);
-            if (lane == 0) s_S[a * spitch + jcol0 + c] = acc;
+            if (lane == 0) s_S[a * spitch + jcol0 + c] = -2.f * acc;
         }
     }
+}
+
+// Row mode, for key shares small enough to sit in registers: NK keys x NS slices of exp(2k) per lane, loaded
+// once (raw: the values as loaded before the staging barrier); then a plain loop over the tile's rows, each
+// row against all NK keys, ending in one transposing reduction of the row's NK sums.  The loop body is short
+// and runs ni times, where streaming mode spends most of a short block's life in code it runs once.
+// Returns true (nothing written) if the operands may leave the range of the factor path.
+template <int NS, int NKM, int NK>
+__device__ __forceinline__ bool fw_rows(const float4 (&raw)[NS][NKM], const float *__restrict__ s_e,
+                                        const float *__restrict__ s_c, int Hp, int ni, float qe_max, float c_max,
+                                        float *__restrict__ s_S, int spitch, int jcol0) {
+    const int lane = lane_id();
+    float fk[NS][4][NK];
+    float kmax = 0.f;
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+        for (int c = 0; c < NK; ++c) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) fk[s][q][c] = fast_exp2(kTwoLog2e * comp(raw[s][c], q));
+            kmax = fmaxf(fmaxf(kmax, fk[s][0][c]), fmaxf(fk[s][1][c], fmaxf(fk[s][2][c], fk[s][3][c])));
+        }
+    if (__any(!(__builtin_fmaf(qe_max, kmax, c_max) < kPairLimit))) return true;
+    constexpr int NPOW = NK <= 1 ? 1 : NK <= 2 ? 2 : NK <= 4 ? 4 : 8;
+    const float *e_col = s_e + 4 * lane;
+    const float *c_col = s_c + 4 * lane;
+    float4 fq = *reinterpret_cast<const float4 *>(e_col);
+    float4 cv = *reinterpret_cast<const float4 *>(c_col);
+    for (int a = 0; a < ni; ++a) {
+        float acc[NK];
+#pragma unroll
+        for (int c = 0; c < NK; ++c) acc[c] = 0.f;
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            // operands of the next slice (of the next row after the last slice; the row past the last one
+            // repeats it) are requested before this slice is evaluated
+            const int a2 = s + 1 < NS ? a : min(a + 1, ni - 1), s2 = s + 1 < NS ? s + 1 : 0;
+            const float4 fq2 = *reinterpret_cast<const float4 *>(e_col + a2 * Hp + s2 * FW_SS);
+            const float4 cv2 = *reinterpret_cast<const float4 *>(c_col + s2 * FW_SS);
+            if constexpr (NK <= 4) {
+                fw_row_keys<NK>(fq, cv, fk[s], acc);
+            } else {                         // groups of two keys so that the temporaries stay few
+#pragma unroll
+                for (int c0 = 0; c0 < NK; c0 += 2) {
+                    if (c0 + 1 < NK) {
+                        float f2[4][2], a2[2] = {acc[c0], acc[c0 + 1]};
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            f2[q][0] = fk[s][q][c0];
+                            f2[q][1] = fk[s][q][c0 + 1];
+                        }
+                        fw_row_keys<2>(fq, cv, f2, a2);
+                        acc[c0] = a2[0];
+                        acc[c0 + 1] = a2[1];
+                    } else {
+                        float f1[4][1], a1[1] = {acc[c0]};
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) f1[q][0] = fk[s][q][c0];
+                        fw_row_keys<1>(fq, cv, f1, a1);
+                        acc[c0] = a1[0];
+                    }
+                }
+            }
+            fq = fq2;
+            cv = cv2;
+        }
+        {
+            float flat[NPOW];
+#pragma unroll
+            for (int c = 0; c < NPOW; ++c) flat[c] = c < NK ? acc[c < NK ? c : 0] : 0.f;
+            const float tot = wave_transpose_sum<NPOW>(flat);
+            const int c = lane / (64 / NPOW);
+            if ((lane % (64 / NPOW)) == 0 && c < NK) s_S[a * spitch + jcol0 + c] = -2.f * tot;
+        }
+    }
+    return false;
+}
+
+template <int NS, int NKM>
+__device__ __forceinline__ bool fw_rows_n(int nk, const float4 (&raw)[NS][NKM], const float *__restrict__ s_e,
+                                          const float *__restrict__ s_c, int Hp, int ni, float qe_max, float c_max,
+                                          float *__restrict__ s_S, int spitch, int jcol0) {
+#define FW_ROWS_CASE(N)                                                                                  \
+    case N:                                                                                              \
+        if constexpr (N <= NKM) return fw_rows<NS, NKM, N>(raw, s_e, s_c, Hp, ni, qe_max, c_max, s_S, spitch, jcol0); \
+        break;
+    switch (nk) {
+        FW_ROWS_CASE(1) FW_ROWS_CASE(2) FW_ROWS_CASE(3) FW_ROWS_CASE(4)
+        FW_ROWS_CASE(5) FW_ROWS_CASE(6) FW_ROWS_CASE(7) FW_ROWS_CASE(8)
+        default: break;
+    }
+#undef FW_ROWS_CASE
+    return false;                            // nk == 0: nothing to do
 }
 
 // Which (sample, row tile) this block works on and the sample's valid keys; see "Placement" at the top.
@@ -286,28 +399,52 @@ __device__ __forceinline__ bool fw_pick_item(const int *__restrict__ key_len, in
             s_pick[1] = (int)((act0 ? key0 : key1) >> 7);
         }
     }
-    __syncthreads();
+    lds_barrier();
     b = s_pick[0];
     L = s_pick[1];
     return true;
 }
 
-template <typename T, int NG>
+template <typename T, int NG, int ROWNS>
 __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
     const T *__restrict__ Qp, const T *__restrict__ Kp, const T *__restrict__ V, const T *__restrict__ v,
     const int *__restrict__ key_len, float *__restrict__ C, float *__restrict__ P,
     int B, int Tq, int Tk, int H, int Dv, int tiles, int Hp, int spitch, int ranked) {
     constexpr int RT = 8 * NG;
+    constexpr bool ROWMODE = ROWNS > 0;                       // ROWNS: slices of h in row mode, 0 = streaming mode
+    constexpr int NKM = fw_row_max_keys(ROWNS);
     extern __shared__ __align__(16) float smem[];
-    float *s_e = smem;                       // [RT][Hp]  exp(2q)
-    float *s_S = s_e + RT * Hp;              // [RT][spitch]  scores, then probabilities
+    float *s_e = smem;                       // [RT][Hp]  exp(2q) / v
+    float *s_c = s_e + RT * Hp;              // [Hp]      1 / v
+    float *s_S = s_c + Hp;                   // [RT][spitch]  scores, then probabilities
+    __shared__ float s_red[2 * FW_W];
 
     const int lane = lane_id(), w = wave_id();
     FW_STAMP(0);
+    // Two blocks share a CU and reach their phases at different times.  The short phases that wait on memory
+    // (placement, staging, softmax, context) go first when they have something to issue; the long score loop
+    // of the other block fills the remaining slots.  Without this a block that is still staging gets almost
+    // no issue slots while its neighbour is in the score loop.
+    __builtin_amdgcn_s_setprio(3);
+
+    // v does not depend on the placement: the first batch of its loads leaves before the key counts are read
+    // (in wave 0, which reads the key counts and must not queue them behind anything, right after that)
+    const int q4 = Hp / 4;                                    // 16-byte columns per row
+    float4 vv[4];
+    auto load_v = [&]() {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = threadIdx.x + u * FW_THREADS;
+            const int h = 4 * (e % q4);
+            vv[u] = (e < RT * q4 && h < H) ? ld4(v, (size_t)h) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    if (w != 0) load_v();
 
     __shared__ int s_pick[2];
     int b, tile, L;
     if (!fw_pick_item(key_len, B, Tk, tiles, ranked, s_pick, b, tile, L)) return;
+    if (w == 0) load_v();
     b = __builtin_amdgcn_readfirstlane(b);
     tile = __builtin_amdgcn_readfirstlane(tile);
     L = __builtin_amdgcn_readfirstlane(L);
@@ -323,67 +460,123 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
         return;
     }
 #ifdef ECHO_TIMING
-    if (threadIdx.x == 0 && blockIdx.x < 16384) g_stamps[blockIdx.x * 8 + 2] = ((long long)b << 40) | ((long long)tile << 24) | ((long long)ni << 16) | L;
+    if (threadIdx.x == 0 && blockIdx.x < 16384) g_stamps[blockIdx.x * 16 + 2] = ((long long)b << 40) | ((long long)tile << 24) | ((long long)ni << 16) | L;
 #endif
 
-    // ---- loads first: this wave's first key slice ...
+    // ---- loads first, in the order of their use: the first batch of query rows (four 16-byte loads per
+    // thread; v was requested before the placement), then this wave's keys (row mode: all of them, streaming
+    // mode: the first slice); then A: exp(2q)/v and 1/v to LDS (rows past ni and columns past H: 0 and kHugeC)
     const T *qb = Qp + ((size_t)b * Tq + r0) * H;
     const T *kb = Kp + (size_t)b * Tk * H;
-    KeyStream<T> ks;
-    {
-        const int k_lo = deal8_begin(L, w);
-        ks.init(kb, v, H, lane, k_lo, deal8_begin(L, w + 1) - k_lo, Hp / FW_SS);
-    }
-    ks.start();
-
-    // ---- A: ... then exp(2q) to LDS (rows past ni and columns past H as zeros), four loads per thread in flight
-    bool big = false;
-    const int q4 = Hp / 4;                                    // 16-byte columns per row
-    for (int e0 = threadIdx.x; e0 < RT * q4; e0 += 4 * FW_THREADS) {
-        float4 x[4];
+    float4 x[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int e = e0 + u * FW_THREADS;
-            const int a = e / q4, h = 4 * (e % q4);
-            x[u] = (e < RT * q4 && a < ni && h < H) ? ld4(qb, (size_t)a * H + h) : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int u = 0; u < 4; ++u) {
+        const int e = threadIdx.x + u * FW_THREADS;
+        const int a = e / q4, h = 4 * (e % q4);
+        x[u] = (e < RT * q4 && h < H && a < ni) ? ld4(qb, (size_t)a * H + h) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    const int k_lo = deal8_begin(L, w);
+    const int nk = deal8_begin(L, w + 1) - k_lo;
+    KeyStream<T> ks;
+    float4 raw[ROWMODE ? ROWNS : 1][NKM];
+    if constexpr (ROWMODE) {
+        // only the wave's own keys are requested (every load takes its turn in the CU's address unit whether
+        // it hits or not); the branches are uniform and everything is awaited at the staging barrier anyway
+#pragma unroll
+        for (int c = 0; c < NKM; ++c) {
+            if (c < nk) {
+#pragma unroll
+                for (int s = 0; s < ROWNS; ++s) {
+                    const int hc = min(s * FW_SS + 4 * lane, H - 4);   // columns past H: see KeyStream::fetch
+                    raw[s][c] = ld4(kb, (size_t)(unsigned)((k_lo + c) * H + hc));
+                }
+            } else {
+#pragma unroll
+                for (int s = 0; s < ROWNS; ++s) raw[s][c] = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+    } else {
+        ks.init(kb, H, lane, k_lo, nk, Hp / FW_SS);
+        ks.start();
+    }
+    FW_STAMP(8);
+
+    float qe_m = 0.f, c_m = 0.f;
+    for (int e0 = threadIdx.x; e0 < RT * q4; e0 += 4 * FW_THREADS) {
+        if (e0 != (int)threadIdx.x) {                          // later batches (H > 1024): loaded here
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e = e0 + u * FW_THREADS;
+                const int a = e / q4, h = 4 * (e % q4);
+                const bool in = e < RT * q4 && h < H;
+                x[u] = (in && a < ni) ? ld4(qb, (size_t)a * H + h) : make_float4(0.f, 0.f, 0.f, 0.f);
+                vv[u] = in ? ld4(v, (size_t)h) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int e = e0 + u * FW_THREADS;
             if (e < RT * q4) {
                 const int a = e / q4, h = 4 * (e % q4);
-                const bool on = a < ni && h < H;
-                big |= fmaxf(fmaxf(fabsf(x[u].x), fabsf(x[u].y)), fmaxf(fabsf(x[u].z), fabsf(x[u].w))) > kFactorLimit;
-                float4 y;
-                y.x = on ? fast_exp2(kTwoLog2e * x[u].x) : 0.f;
-                y.y = on ? fast_exp2(kTwoLog2e * x[u].y) : 0.f;
-                y.z = on ? fast_exp2(kTwoLog2e * x[u].z) : 0.f;
-                y.w = on ? fast_exp2(kTwoLog2e * x[u].w) : 0.f;
-                *reinterpret_cast<float4 *>(s_e + a * Hp + h) = y;
+                const bool row_on = a < ni;
+                float y[4], cc[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float vq = comp(vv[u], q);
+                    const bool v_on = fabsf(vq) >= kTinyV;         // false for columns past H (v read as 0)
+                    cc[q] = v_on ? fast_rcp(vq) : kHugeC;
+                    y[q] = (v_on && row_on) ? fast_exp2(kTwoLog2e * comp(x[u], q)) * cc[q] : 0.f;
+                    qe_m = fmaxf(qe_m, fabsf(y[q]));
+                    // a |v| so large that products of two 1/v could underflow also goes to the exact path
+                    c_m = fmaxf(c_m, fabsf(vq) > 1e15f ? INFINITY : fabsf(cc[q]));
+                    if (y[q] != y[q]) qe_m = INFINITY;              // NaN input: exact path (fmaxf drops NaN)
+                }
+                *reinterpret_cast<float4 *>(s_e + a * Hp + h) = make_float4(y[0], y[1], y[2], y[3]);
+                if (a == 0) *reinterpret_cast<float4 *>(s_c + h) = make_float4(cc[0], cc[1], cc[2], cc[3]);
             }
         }
     }
-    const bool qbig = __syncthreads_or(big) != 0;
+    FW_STAMP(10);
+    qe_m = wave_max(qe_m);
+    c_m = wave_max(c_m);
+    if (lane == 0) {
+        s_red[w] = qe_m;
+        s_red[FW_W + w] = c_m;
+    }
+    lds_barrier();
+    float qe_max = 0.f, c_max = 0.f;
+#pragma unroll
+    for (int k = 0; k < FW_W; ++k) {
+        qe_max = fmaxf(qe_max, s_red[k]);
+        c_max = fmaxf(c_max, s_red[FW_W + k]);
+    }
     FW_STAMP(3);
 
-    // ---- B: scores, this wave's keys in passes of up to FW_NJ
-    for (int p = 0; p < ks.npass; ++p) {
-        const int j0 = ks.pass_begin(p);
-        const int nj = ks.pass_begin(p + 1) - j0;              // 1..FW_NJ
-        bool redo = true;
-#define FW_CASE(N)                                                                            \
-    case N:                                                                                   \
-        redo = (ni == RT)       ? fw_pass<T, NG, N, RT>(s_e, Hp, ni, ks, s_S, spitch, j0)     \
-               : (ni == RT - 1) ? fw_pass<T, NG, N, RT - 1>(s_e, Hp, ni, ks, s_S, spitch, j0) \
-                                : fw_pass<T, NG, N, 0>(s_e, Hp, ni, ks, s_S, spitch, j0);     \
+    // ---- B: scores of this wave's keys
+    __builtin_amdgcn_s_setprio(0);
+    if constexpr (ROWMODE) {
+        if (fw_rows_n<ROWNS, NKM>(nk, raw, s_e, s_c, Hp, ni, qe_max, c_max, s_S, spitch, k_lo))
+            fw_pass_exact<T>(qb, ni, kb + (size_t)k_lo * H, nk, H, v, s_S, spitch, k_lo);
+    } else {
+        for (int p = 0; p < ks.npass; ++p) {                   // passes of up to FW_NJ keys
+            const int j0 = ks.pass_begin(p);
+            const int nj = ks.pass_begin(p + 1) - j0;          // 1..FW_NJ
+            bool redo = true;
+#define FW_CASE(N)                                                                                          \
+    case N:                                                                                                 \
+        redo = (ni == RT)       ? fw_pass<T, NG, N, RT>(s_e, s_c, Hp, ni, ks, qe_max, c_max, s_S, spitch, j0)     \
+               : (ni == RT - 1) ? fw_pass<T, NG, N, RT - 1>(s_e, s_c, Hp, ni, ks, qe_max, c_max, s_S, spitch, j0) \
+                                : fw_pass<T, NG, N, 0>(s_e, s_c, Hp, ni, ks, qe_max, c_max, s_S, spitch, j0);     \
         break;
-        switch (nj) {
-            FW_CASE(1) FW_CASE(2) FW_CASE(3) FW_CASE(4)
-            default: break;
-        }
+            switch (nj) {
+                FW_CASE(1) FW_CASE(2) FW_CASE(3) FW_CASE(4)
+                default: break;
+            }
 #undef FW_CASE
-        if (redo || qbig) fw_pass_exact<T>(qb, ni, kb + (size_t)j0 * H, nj, H, v, s_S, spitch, j0);
+            if (redo) fw_pass_exact<T>(qb, ni, kb + (size_t)j0 * H, nj, H, v, s_S, spitch, j0);
+        }
     }
+    __builtin_amdgcn_s_setprio(3);
 
     // first batch of value rows for the context phase leaves before the softmax
     const T *vb = V + (size_t)b * Tk * Dv;
@@ -398,7 +591,7 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
         for (int kk = 0; kk < FW_KB; ++kk) dst[kk] = ld(vb, (size_t)(unsigned)(min(kb0 + kk, L - 1) * Dv + n));
     };
     v_fetch(vcur, min(w, n_grp - 1), 0);
-    __syncthreads();
+    lds_barrier();
     FW_STAMP(4);
 
     // ---- C: softmax, waves take rows in turn; probabilities replace the scores in LDS
@@ -425,7 +618,7 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
             for (int j = lane; j < Lp; j += 64) srow[j] = 0.f;
         }
     }
-    __syncthreads();
+    lds_barrier();
     FW_STAMP(5);
 
     // ---- D: context rows = P V.  A wave takes 64 columns at a time; lane l owns column n0 + l.
@@ -482,7 +675,7 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
         unsigned hw, xcc;
         asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
         asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-        g_stamps[blockIdx.x * 8 + 7] = ((long long)xcc << 32) | hw;
+        g_stamps[blockIdx.x * 16 + 7] = ((long long)xcc << 32) | hw;
     }
 #endif
 }
@@ -499,14 +692,22 @@ extern "C" int echo_debug_stamps(long long *host, int n) {
 static size_t fwd_lds_bytes(const AttnShape &s, int ng) {
     const int Hp = (s.H + FW_SS - 1) / FW_SS * FW_SS;
     const int spitch = ((s.Tk + 3) & ~3) + 4;
-    return (size_t)(8 * ng) * (Hp + spitch) * sizeof(float);
+    return ((size_t)(8 * ng) * (Hp + spitch) + Hp) * sizeof(float);
 }
 
 bool fwd_fused_supported(const AttnShape &s) {
     return s.H % 4 == 0 && fwd_lds_bytes(s, 1) <= 150 * 1024;
 }
 
-template <typename T, int NG>
+// Row mode needs the longest key share of a wave, ceil(Tk / 8) keys, times the slices of h to fit the
+// registers set aside for it; it is built for 1, 2 and 4 slices (H up to 256, 512, 1024).
+static int fwd_row_mode_slices(const AttnShape &s) {
+    const int ns = (s.H + FW_SS - 1) / FW_SS;
+    if (ns != 1 && ns != 2 && ns != 4) return 0;
+    return (s.Tk + FW_W - 1) / FW_W <= fw_row_max_keys(ns) ? ns : 0;
+}
+
+template <typename T, int NG, int ROWNS>
 static hipError_t launch_fwd_fused_t(const AttnShape &s, const void *Qp, const void *Kp, const void *V, const void *v,
                                      const int *key_len, float *C, float *P, hipStream_t st) {
     constexpr int RT = 8 * NG;
@@ -514,7 +715,7 @@ static hipError_t launch_fwd_fused_t(const AttnShape &s, const void *Qp, const v
     const int spitch = ((s.Tk + 3) & ~3) + 4;
     const size_t lds = fwd_lds_bytes(s, NG);
     if (lds > 48 * 1024) {   // beyond the default dynamic LDS limit: raise it (no state is kept between calls)
-        hipError_t e = hipFuncSetAttribute((const void *)k_fwd_fused<T, NG>,
+        hipError_t e = hipFuncSetAttribute((const void *)k_fwd_fused<T, NG, ROWNS>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
@@ -523,16 +724,27 @@ static hipError_t launch_fwd_fused_t(const AttnShape &s, const void *Qp, const v
     const long long grid = (long long)FW_XCD * samples_per_xcd * tiles;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     const int ranked = s.B <= FW_MAX_RANKED_B ? 1 : 0;
-    k_fwd_fused<T, NG><<<(unsigned)grid, FW_THREADS, lds, st>>>((const T *)Qp, (const T *)Kp, (const T *)V,
-                                                               (const T *)v, key_len, C, P, s.B, s.Tq, s.Tk, s.H, s.Dv,
-                                                               tiles, Hp, spitch, ranked);
+    k_fwd_fused<T, NG, ROWNS><<<(unsigned)grid, FW_THREADS, lds, st>>>(
+        (const T *)Qp, (const T *)Kp, (const T *)V, (const T *)v, key_len, C, P, s.B, s.Tq, s.Tk, s.H, s.Dv, tiles, Hp,
+        spitch, ranked);
     return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t launch_fwd_fused_mode(const AttnShape &s, const void *Qp, const void *Kp, const void *V,
+                                        const void *v, const int *key_len, float *C, float *P, hipStream_t st) {
+    switch (fwd_row_mode_slices(s)) {
+        case 1: return launch_fwd_fused_t<T, 1, 1>(s, Qp, Kp, V, v, key_len, C, P, st);
+        case 2: return launch_fwd_fused_t<T, 1, 2>(s, Qp, Kp, V, v, key_len, C, P, st);
+        case 4: return launch_fwd_fused_t<T, 1, 4>(s, Qp, Kp, V, v, key_len, C, P, st);
+        default: return launch_fwd_fused_t<T, 1, 0>(s, Qp, Kp, V, v, key_len, C, P, st);
+    }
 }
 
 hipError_t launch_fwd_fused(const AttnShape &s, const void *Qp, const void *Kp, const void *V, const void *v,
                             const int *key_len, float *C, float *P, hipStream_t st) {
-    return s.bf16 ? launch_fwd_fused_t<bf16_t, 1>(s, Qp, Kp, V, v, key_len, C, P, st)
-                  : launch_fwd_fused_t<float, 1>(s, Qp, Kp, V, v, key_len, C, P, st);
+    return s.bf16 ? launch_fwd_fused_mode<bf16_t>(s, Qp, Kp, V, v, key_len, C, P, st)
+                  : launch_fwd_fused_mode<float>(s, Qp, Kp, V, v, key_len, C, P, st);
 }
 
 }  // namespace echo
