@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <mutex>
 #include <string>
 #include <vector>
@@ -40,7 +41,7 @@ echo_status_t check_desc(const echo_attn_desc_t *d, AttnShape *s) {
 inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 struct BwdWs {
-    size_t ds_off, rowsum_off, dvpart_off, order_off, total;
+    size_t ds_off, rowsum_off, dvpart_off, order_off, dvflag_off, total;
 };
 BwdWs bwd_layout(const AttnShape &s) {
     BwdWs w;
@@ -48,7 +49,8 @@ BwdWs bwd_layout(const AttnShape &s) {
     w.rowsum_off = align_up((size_t)s.B * s.Tq * echo::ds_pitch(s.Tk) * sizeof(float));
     w.dvpart_off = w.rowsum_off + align_up((size_t)s.B * s.Tq * sizeof(float));
     w.order_off = w.dvpart_off + align_up((size_t)s.B * s.H * sizeof(float));
-    w.total = w.order_off + align_up((size_t)s.B * sizeof(int));
+    w.dvflag_off = w.order_off + align_up((size_t)s.B * sizeof(int));
+    w.total = w.dvflag_off + align_up((size_t)((s.H + 63) / 64) * s.B * sizeof(unsigned long long));
     return w;
 }
 size_t fwd_bytes(const AttnShape &s) { return align_up((size_t)s.B * s.Tq * s.Tk * sizeof(float)); }
@@ -78,6 +80,11 @@ struct Timed {
 };
 
 thread_local std::string g_last_error;
+
+// Number of a backward launch: blocks of one launch recognise each other's flags in the workspace by it, so
+// the flags need no clearing beforehand, whatever the workspace holds.  Odd, hence never 0 (the cleared state).
+std::atomic<unsigned long long> g_launch_number{0x9E3779B97F4A7C15ull};
+unsigned long long next_launch_number() { return g_launch_number.fetch_add(2, std::memory_order_relaxed) | 1ull; }
 
 #define ECHO_LAUNCH(NAME, CALL)                                                  \
     do {                                                                         \
@@ -138,11 +145,11 @@ echo_status_t bwd_impl(const echo_attn_desc_t *desc, const float *dContext, cons
     float *rowsum = reinterpret_cast<float *>(ws + lay.rowsum_off);
     float *dv_part = reinterpret_cast<float *>(ws + lay.dvpart_off);
     int *order = reinterpret_cast<int *>(ws + lay.order_off);
+    unsigned long long *dv_flag = reinterpret_cast<unsigned long long *>(ws + lay.dvflag_off);
     ECHO_LAUNCH("bwd_pre", echo::launch_bwd_pre(s, dContext, V, P, key_len, dS, rowsum, order, dV, st));
     ECHO_LAUNCH(use_map ? "recompute_stash" : "recompute",
                 echo::launch_recompute(s, Qp, Kp, v, order, dS, rowsum, use_map ? tmap : nullptr, dQp, dKp, dv_part,
-                                       st));
-    ECHO_LAUNCH("dv_reduce", echo::launch_dv_reduce(s, dv_part, dv, st));
+                                       dv_flag, next_launch_number(), dv, st));
     return ECHO_OK;
 }
 

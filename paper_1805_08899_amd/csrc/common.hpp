@@ -164,6 +164,30 @@ __device__ __forceinline__ float wave_transpose_sum(float (&a)[N]) {
     return a[0];
 }
 
+// Barrier for data exchanged through LDS only: waits for this wave's LDS operations, not for its global
+// loads and stores (__syncthreads() would also wait for every prefetch and store in flight).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Accesses that other blocks of the same launch must see (or that must see theirs): device-scope relaxed
+// atomics, which go through to the memory side of the per-XCD L2 caches instead of staying in one of them.
+// Ordering between them is the program order of the issuing wave plus an explicit wait on the memory counter.
+__device__ __forceinline__ void store_agent(float *p, float x) {
+    __hip_atomic_store(p, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_agent(const float *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_agent(unsigned long long *p, unsigned long long x) {
+    __hip_atomic_store(p, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long load_agent(const unsigned long long *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void wait_all_memory_ops() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// A wait on another block's flag gives up after this many ticks of the 100 MHz wall clock (2 s), so that every
+// wave ends whatever happens; the results of that launch are then marked invalid (NaN).
+constexpr long long kSpinLimitTicks = 200000000LL;
+
 __device__ __forceinline__ int clamp_len(int len, int Tk) { return len < 0 ? 0 : (len > Tk ? Tk : len); }
 
 // n items dealt to the 8 waves of a block as contiguous ranges of n / 8 or n / 8 + 1 items: first item of wave w

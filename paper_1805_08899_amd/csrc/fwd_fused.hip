@@ -67,10 +67,6 @@ constexpr int fw_row_max_keys(int ns) { return ns <= 0 ? 1 : (FW_ROW_REGS / ns >
 
 __device__ __forceinline__ float comp(const float4 &x, int c) { return c == 0 ? x.x : c == 1 ? x.y : c == 2 ? x.z : x.w; }
 
-// Barrier for data exchanged through LDS only: waits for this wave's LDS operations, not for its global
-// loads and stores (__syncthreads() would also wait for every prefetch in flight).
-__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
 // Pairs of reciprocals share one division (see B at the top): the product a0 a1 must stay finite.
 // |a| <= max|1/v| + max|exp(2q)/v| max exp(2k); a pass is evaluated by the factor path only while this
 // bound is below kPairLimit = sqrt(FLT_MAX) (with a little room).  An entry of v below kTinyV in magnitude

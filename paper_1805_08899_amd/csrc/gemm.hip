@@ -193,7 +193,7 @@ __device__ __forceinline__ void dscore_block(const float *__restrict__ dC, const
             }
         }
     }
-    __syncthreads();
+    lds_barrier();
 
     for (int rr = w; rr < 16; rr += 4) {
         const int i = i0 + rr;
@@ -301,7 +301,7 @@ __device__ __forceinline__ void dscore_block_dsplit(const float *__restrict__ dC
         for (int u = 0; u < U; ++u) bcur[u] = bnxt[u];
     }
     PRE_STAMP(2);
-    __syncthreads();
+    lds_barrier();
     PRE_STAMP(3);
 
     // the four rows together: r = sum_j P dP and sum_j dS by transposing reductions (sum of row t ends up in
@@ -356,7 +356,7 @@ __device__ __forceinline__ void rank_block(const int *__restrict__ key_len, int 
                                            int *__restrict__ s_len, int B, int Tk, int sorted, int fold) {
     if (sorted)
         for (int o = threadIdx.x; o < B; o += 256) s_len[o] = clamp_len(key_len[o], Tk);
-    __syncthreads();
+    lds_barrier();
     const int half = (B + 1) / 2;
     for (int cand = threadIdx.x; cand < B; cand += 256) {
         int r = cand;

@@ -36,11 +36,14 @@ hipError_t launch_context(const AttnShape &s, const float *P, const void *V, con
 constexpr int kMaxSortedB = 1024;
 hipError_t launch_bwd_pre(const AttnShape &s, const float *dC, const void *V, const float *P, const int *key_len,
                           float *dS, float *ds_rowsum, int *order, float *dV, hipStream_t st);
-// B3  fused recompute: dQp, dKp, per-sample partials of dv (dv_part [B,H]);
+// B3 + B4  fused recompute: dQp, dKp, per-sample partials of dv (dv_part [B,H]) and, by the blocks that start
+// last, dv[h] = sum_b dv_part[b,h] in index order (added to dv if s.acc).  dv_flag: ceil(H/64) x B words of
+// workspace in any state; epoch: a number no earlier launch on this workspace used (never 0).
 // tmap != nullptr reads tanh from the stashed map instead of recomputing it
 hipError_t launch_recompute(const AttnShape &s, const void *Qp, const void *Kp, const void *v, const int *order,
                             const float *dS, const float *ds_rowsum, const float *tmap, float *dQp, float *dKp,
-                            float *dv_part, hipStream_t st);
+                            float *dv_part, unsigned long long *dv_flag, unsigned long long epoch, float *dv,
+                            hipStream_t st);
 // B4  dv[h] = sum_b dv_part[b,h], fixed order
 hipError_t launch_dv_reduce(const AttnShape &s, const float *dv_part, float *dv, hipStream_t st);
 // One decoder step (Tq = 1) of the backward pass in one launch; dKp, dV and dv_part [B,H] are added to.

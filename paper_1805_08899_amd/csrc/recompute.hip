@@ -118,7 +118,8 @@ template <typename T, bool STASH>
 __global__ __launch_bounds__(RC_THREADS) void k_recompute(
     const T *__restrict__ Qp, const T *__restrict__ Kp, const T *__restrict__ v,
     const int *__restrict__ order, const float *__restrict__ dS, const float *__restrict__ ds_rowsum,
-    const float *__restrict__ tmap, float *__restrict__ dQp, float *__restrict__ dKp, float *__restrict__ dv_part,
+    const float *__restrict__ tmap, float *__restrict__ dQp, float *__restrict__ dKp, float *dv_part,
+    unsigned long long *dv_flag, unsigned long long epoch, float *__restrict__ dv,
     int Tq, int Tk, int H, int pitch, int rows_per_pass, int acc) {
     // Key tile staged once per block, double buffered: exp(2k) for the factor
     // path, 2 log2e k for the exact path, and per key a flag "beyond the factor limit".
@@ -129,6 +130,7 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
     __shared__ float s_part[2][RC_W][RC_RJ][64];
     __shared__ float s_dv[RC_W][64];
     __shared__ float s_rowsum;
+    __shared__ int s_seen[RC_W];
 
     RC_STAMP(0);
     // slot -> sample (the heaviest samples start first) and its clamped key length, packed by the ranking block
@@ -213,7 +215,7 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
             }
             const bool wave_qbig = __any(qbig);
             commit(0, 0);
-            __syncthreads();
+            lds_barrier();
             if (pass == 0) RC_STAMP(2);
 
             for (int jt = 0; jt < n_jt; ++jt) {
@@ -256,7 +258,7 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
                 if (more) commit(jt + 1, buf ^ 1);
 #pragma unroll
                 for (int c = 0; c < RC_RJ; ++c) s_part[buf][w][c][lane] = accK[c];
-                __syncthreads();
+                lds_barrier();
                 // wave w finishes key j0 + w of this tile: sum over the waves in fixed order
                 const int j = j0 + w;
                 float tot = 0.f;
@@ -274,22 +276,71 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
                 for (int a = 0; a < RC_RI; ++a)
                     if (a < ni) store_streaming(&dQb[(size_t)(i0 + a) * H + h], v4 * accQ[a]);
             }
-            __syncthreads();   // the next pass restages buffer 0 and reuses s_part
+            lds_barrier();   // the next pass restages buffer 0 and reuses s_part
         }
     }
 
     RC_STAMP(3);
     // dv partial of this sample: sum dS t = sum dS - 2 sum dS r
     s_dv[w][lane] = (accV[0] + accV[1]) + (accV[2] + accV[3]);
-    __syncthreads();
+    lds_barrier();
+    const int n_slots = gridDim.y;
+    unsigned long long *flags = dv_flag + (size_t)blockIdx.x * n_slots;      // of this slice of h, one per slot
     if (w == 0) {
         if (hv) {
             float tot = 0.f;
 #pragma unroll
             for (int w2 = 0; w2 < RC_W; ++w2) tot += s_dv[w2][lane];
-            dv_part[(size_t)b * H + h] = __builtin_fmaf(-2.f, tot, s_rowsum);
+            store_agent(&dv_part[(size_t)b * H + h], __builtin_fmaf(-2.f, tot, s_rowsum));
+        }
+        // B4 without a launch of its own: the part is published (written through, awaited, then flagged with
+        // this launch's number), and the block of the last slot, which starts last and holds the lightest
+        // sample, adds the parts of its slice of h once all of them are flagged.
+        wait_all_memory_ops();
+        if (lane == 0) store_agent(&flags[blockIdx.y], epoch);
+    }
+    if ((int)blockIdx.y != n_slots - 1) return;
+    RC_STAMP(5);
+    lds_barrier();                                   // s_dv is reused below
+    const long long t_wait0 = wall_clock64();
+    int seen = 1;
+    for (int s0 = threadIdx.x; s0 < n_slots; s0 += RC_THREADS) {
+        while (load_agent(&flags[s0]) != epoch) {
+            __builtin_amdgcn_s_sleep(4);
+            if (wall_clock64() - t_wait0 > kSpinLimitTicks) {
+                seen = 0;
+                break;
+            }
         }
     }
+    // samples in index order, eight groups of them added group by group: the order of additions is fixed
+    float part = 0.f;
+    s_seen[w] = __all(seen) ? 1 : 0;
+    lds_barrier();
+    bool all_seen = true;
+#pragma unroll
+    for (int w2 = 0; w2 < RC_W; ++w2) all_seen = all_seen && s_seen[w2] != 0;
+    if (hv && all_seen) {
+        for (int b0 = w; b0 < n_slots; b0 += 8 * RC_W) {
+            float x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                x[u] = (b0 + RC_W * u < n_slots) ? load_agent(&dv_part[(size_t)(b0 + RC_W * u) * H + h]) : 0.f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) part += x[u];
+        }
+    }
+    s_dv[w][lane] = part;
+    lds_barrier();
+    if (w == 0 && hv) {
+        float tot = 0.f;
+#pragma unroll
+        for (int w2 = 0; w2 < RC_W; ++w2) tot += s_dv[w2][lane];
+        if (!all_seen) tot = __builtin_nanf("");      // a part never arrived: make the failure visible
+        dv[h] = acc ? dv[h] + tot : tot;
+    }
+    // leave the flags cleared: a replay of a captured launch carries the same launch number
+    for (int s0 = threadIdx.x; s0 < n_slots; s0 += RC_THREADS) store_agent(&flags[s0], 0ull);
     RC_STAMP(4);
 #ifdef ECHO_TIMING
     {
@@ -314,27 +365,33 @@ extern "C" int echo_debug_stamps_rc(long long *host, int n) {
 template <typename T>
 static hipError_t launch_recompute_t(const AttnShape &s, const void *Qp, const void *Kp, const void *v,
                                      const int *order, const float *dS, const float *ds_rowsum, const float *tmap,
-                                     float *dQp, float *dKp, float *dv_part, hipStream_t st) {
+                                     float *dQp, float *dKp, float *dv_part, unsigned long long *dv_flag,
+                                     unsigned long long epoch, float *dv, hipStream_t st) {
     const int max_rows = RC_W * RC_RI;
     const int n_pass = (s.Tq + max_rows - 1) / max_rows;
     const int rows_per_pass = (s.Tq + n_pass - 1) / n_pass;
     dim3 grid((s.H + 63) / 64, s.B);
     if (tmap)
         k_recompute<T, true><<<grid, RC_THREADS, 0, st>>>((const T *)Qp, (const T *)Kp, (const T *)v, order, dS,
-                                                          ds_rowsum, tmap, dQp, dKp, dv_part, s.Tq, s.Tk, s.H,
-                                                          ds_pitch(s.Tk), rows_per_pass, s.acc ? 1 : 0);
+                                                          ds_rowsum, tmap, dQp, dKp, dv_part, dv_flag, epoch, dv,
+                                                          s.Tq, s.Tk, s.H, ds_pitch(s.Tk), rows_per_pass,
+                                                          s.acc ? 1 : 0);
     else
         k_recompute<T, false><<<grid, RC_THREADS, 0, st>>>((const T *)Qp, (const T *)Kp, (const T *)v, order, dS,
-                                                           ds_rowsum, tmap, dQp, dKp, dv_part, s.Tq, s.Tk, s.H,
-                                                           ds_pitch(s.Tk), rows_per_pass, s.acc ? 1 : 0);
+                                                           ds_rowsum, tmap, dQp, dKp, dv_part, dv_flag, epoch, dv,
+                                                           s.Tq, s.Tk, s.H, ds_pitch(s.Tk), rows_per_pass,
+                                                           s.acc ? 1 : 0);
     return hipGetLastError();
 }
 
 hipError_t launch_recompute(const AttnShape &s, const void *Qp, const void *Kp, const void *v, const int *order,
                             const float *dS, const float *ds_rowsum, const float *tmap, float *dQp, float *dKp,
-                            float *dv_part, hipStream_t st) {
-    return s.bf16 ? launch_recompute_t<bf16_t>(s, Qp, Kp, v, order, dS, ds_rowsum, tmap, dQp, dKp, dv_part, st)
-                  : launch_recompute_t<float>(s, Qp, Kp, v, order, dS, ds_rowsum, tmap, dQp, dKp, dv_part, st);
+                            float *dv_part, unsigned long long *dv_flag, unsigned long long epoch, float *dv,
+                            hipStream_t st) {
+    return s.bf16 ? launch_recompute_t<bf16_t>(s, Qp, Kp, v, order, dS, ds_rowsum, tmap, dQp, dKp, dv_part, dv_flag,
+                                               epoch, dv, st)
+                  : launch_recompute_t<float>(s, Qp, Kp, v, order, dS, ds_rowsum, tmap, dQp, dKp, dv_part, dv_flag,
+                                              epoch, dv, st);
 }
 
 }  // namespace echo
