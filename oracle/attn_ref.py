@@ -5,7 +5,7 @@ a time so that the largest live array is one sample's Tq x Tk x H map.  Shares
 no code with the HIP path.
 
 What is computed (the recompute-in-backward of the paper changes what is kept
-in memory, not any value -- Section 8, "Algorithm Changes"):
+in memory, not any value -- Section 7, Related Work, "Algorithm Changes"):
 
   scoring       a broadcast add of every query row with every key row followed
                 by tanh (Section 4.1, the figure with T tensors of shape [N]

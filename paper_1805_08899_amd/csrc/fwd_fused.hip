@@ -42,15 +42,6 @@ namespace echo {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-#ifdef ECHO_TIMING   // development aid: per-block phase time stamps (100 MHz counter), read back with echo_debug_stamps
-__device__ long long g_stamps[16384 * 16];
-#define FW_STAMP(k)                                                                                  \
-    do {                                                                                             \
-        if (threadIdx.x == 0 && blockIdx.x < 16384) g_stamps[blockIdx.x * 16 + (k)] = wall_clock64(); \
-    } while (0)
-#else
-#define FW_STAMP(k)
-#endif
 
 constexpr int FW_W = 8;          // waves per block (deal8_begin deals the keys to eight)
 constexpr int FW_THREADS = 64 * FW_W;
@@ -416,7 +407,6 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
     __shared__ float s_red[2 * FW_W];
 
     const int lane = lane_id(), w = wave_id();
-    FW_STAMP(0);
     // Two blocks share a CU and reach their phases at different times.  The short phases that wait on memory
     // (placement, staging, softmax, context) go first when they have something to issue; the long score loop
     // of the other block fills the remaining slots.  Without this a block that is still staging gets almost
@@ -446,7 +436,6 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
     L = __builtin_amdgcn_readfirstlane(L);
     const int r0 = (int)(((long long)Tq * tile) / tiles);      // rows are split evenly over the tiles
     const int ni = (int)(((long long)Tq * (tile + 1)) / tiles) - r0;   // 1..RT
-    FW_STAMP(1);
 
     float *Pb = P + ((size_t)b * Tq + r0) * Tk;
     float *Cb = C + ((size_t)b * Tq + r0) * Dv;
@@ -455,9 +444,6 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
         for (int e = threadIdx.x; e < ni * Dv; e += FW_THREADS) Cb[e] = 0.f;
         return;
     }
-#ifdef ECHO_TIMING
-    if (threadIdx.x == 0 && blockIdx.x < 16384) g_stamps[blockIdx.x * 16 + 2] = ((long long)b << 40) | ((long long)tile << 24) | ((long long)ni << 16) | L;
-#endif
 
     // ---- loads first, in the order of their use: the first batch of query rows (four 16-byte loads per
     // thread; v was requested before the placement), then this wave's keys (row mode: all of them, streaming
@@ -495,7 +481,6 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
         ks.init(kb, H, lane, k_lo, nk, Hp / FW_SS);
         ks.start();
     }
-    FW_STAMP(8);
 
     float qe_m = 0.f, c_m = 0.f;
     for (int e0 = threadIdx.x; e0 < RT * q4; e0 += 4 * FW_THREADS) {
@@ -532,7 +517,6 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
             }
         }
     }
-    FW_STAMP(10);
     qe_m = wave_max(qe_m);
     c_m = wave_max(c_m);
     if (lane == 0) {
@@ -546,7 +530,6 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
         qe_max = fmaxf(qe_max, s_red[k]);
         c_max = fmaxf(c_max, s_red[FW_W + k]);
     }
-    FW_STAMP(3);
 
     // ---- B: scores of this wave's keys
     __builtin_amdgcn_s_setprio(0);
@@ -588,7 +571,6 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
     };
     v_fetch(vcur, min(w, n_grp - 1), 0);
     lds_barrier();
-    FW_STAMP(4);
 
     // ---- C: softmax, waves take rows in turn; probabilities replace the scores in LDS
     for (int a = w; a < RT; a += FW_W) {
@@ -615,7 +597,6 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
         }
     }
     lds_barrier();
-    FW_STAMP(5);
 
     // ---- D: context rows = P V.  A wave takes 64 columns at a time; lane l owns column n0 + l.
     // One 4x4x1 MFMA multiplies 4 rows of P (replicated over the 16 lane groups) with one V value per lane.
@@ -665,22 +646,8 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
         g = g2;
         kb0 = kb2;
     }
-    FW_STAMP(6);
-#ifdef ECHO_TIMING
-    if (threadIdx.x == 0 && blockIdx.x < 16384) {
-        unsigned hw, xcc;
-        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
-        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-        g_stamps[blockIdx.x * 16 + 7] = ((long long)xcc << 32) | hw;
-    }
-#endif
 }
 
-#ifdef ECHO_TIMING
-extern "C" int echo_debug_stamps(long long *host, int n) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_stamps), (size_t)n * sizeof(long long));
-}
-#endif
 
 // Rows per block: 8.  (16 rows halve the exponentials of K per score, but need twice the accumulators; with
 // two waves per SIMD instead of four that measured 20-25 % slower on the large workloads.)

@@ -216,18 +216,6 @@ __device__ __forceinline__ void dscore_block(const float *__restrict__ dC, const
     }
 }
 
-#ifdef ECHO_TIMING   // development aid: per-block time stamps (100 MHz counter), read back with echo_debug_stamps_pre
-__device__ long long g_pre_stamps[16384 * 4];
-#define PRE_STAMP(k)                                                                                      \
-    do {                                                                                                  \
-        if (threadIdx.x == 0 && blockIdx.x < 16384) g_pre_stamps[blockIdx.x * 4 + (k)] = wall_clock64();  \
-    } while (0)
-extern "C" int echo_debug_stamps_pre(long long *host, int n) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_pre_stamps), (size_t)n * sizeof(long long));
-}
-#else
-#define PRE_STAMP(k)
-#endif
 
 // The same for short key axes (Tk <= kDsplitMaxTk): latency, not arithmetic, decides here, so the four waves
 // split d instead of the key tiles.  Wave w owns the columns d of every fourth 128-wide chunk, keeps its slice
@@ -300,9 +288,7 @@ __device__ __forceinline__ void dscore_block_dsplit(const float *__restrict__ dC
 #pragma unroll
         for (int u = 0; u < U; ++u) bcur[u] = bnxt[u];
     }
-    PRE_STAMP(2);
     lds_barrier();
-    PRE_STAMP(3);
 
     // the four rows together: r = sum_j P dP and sum_j dS by transposing reductions (sum of row t ends up in
     // lanes 16 t .. 16 t + 15), so the exchanges of the rows overlap instead of queueing behind each other
@@ -384,7 +370,6 @@ __global__ __launch_bounds__(256, 3) void k_bwd_pre(const float *__restrict__ dC
                                                  int Tq, int Tk, int Dv, int pitch, int s_tiles, int v_xt, int v_yt, int acc) {
     extern __shared__ float s_dp[];           // [16][pitch16], four such planes when Tk <= kDsplitMaxTk
     __shared__ int s_len[kMaxSortedB];
-    PRE_STAMP(0);
     // The hardware deals blocks to the eight XCDs round-robin, so block id mod 8 names the XCD.  Sample b is
     // worked on by XCD b mod 8 only: its dC, V and P then pass through one L2 instead of eight.  Within an XCD the
     // long dS blocks of all its samples come first, then the dV blocks; the last block of the grid ranks.
@@ -394,7 +379,6 @@ __global__ __launch_bounds__(256, 3) void k_bwd_pre(const float *__restrict__ dC
     const int per_xcd = spx * (s_tiles + per_b);
     if ((int)blockIdx.x == kXcd * per_xcd) {
         rank_block(key_len, order, s_len, B, Tk, sorted, fold);
-        PRE_STAMP(1);
         return;
     }
     const int xcd = blockIdx.x % kXcd;
@@ -406,14 +390,12 @@ __global__ __launch_bounds__(256, 3) void k_bwd_pre(const float *__restrict__ dC
             dscore_block_dsplit<TV>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
         else
             dscore_block<TV>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
-        PRE_STAMP(1);
         return;
     }
     li -= spx * s_tiles;
     const int b = xcd + kXcd * (li / per_b), rem = li % per_b;
     if (b >= B) return;
     pv_block<float, true>(P, dC, key_len, dV, Tq, Tk, Dv, b, rem / v_xt, rem % v_xt, acc);
-    PRE_STAMP(1);
 }
 
 hipError_t launch_bwd_pre(const AttnShape &s, const float *dC, const void *V, const float *P, const int *key_len,

@@ -34,16 +34,6 @@ static_assert(RC_W == 8, "rows are dealt to eight waves");
 
 enum RcMode { RC_FACTOR = 0, RC_EXACT = 1, RC_STASH = 2 };
 
-#ifdef ECHO_TIMING   // development aid: per-block phase time stamps (100 MHz counter), read back with echo_debug_stamps_rc
-__device__ long long g_rc_stamps[16384 * 8];
-#define RC_STAMP(k)                                                                                        \
-    do {                                                                                                   \
-        const int bid_ = blockIdx.y * gridDim.x + blockIdx.x;                                              \
-        if (threadIdx.x == 0 && bid_ < 16384) g_rc_stamps[bid_ * 8 + (k)] = wall_clock64();                \
-    } while (0)
-#else
-#define RC_STAMP(k)
-#endif
 
 // One RI x RJ register tile.  NI = number of live rows (compile time so the
 // accumulators stay in registers and the NI*RJ chains interleave freely).
@@ -132,7 +122,6 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
     __shared__ float s_rowsum;
     __shared__ int s_seen[RC_W];
 
-    RC_STAMP(0);
     // slot -> sample (the heaviest samples start first) and its clamped key length, packed by the ranking block
     const int packed = order[blockIdx.y];
     const int b = packed & 0xffff, L = packed >> 16;
@@ -162,7 +151,6 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
         if (lane == 0) s_rowsum = rs;
     }
 
-    RC_STAMP(1);
     float accV[4] = {0.f, 0.f, 0.f, 0.f};
     if (L > 0) {
         const T *qb = Qp + (size_t)b * Tq * H;
@@ -216,7 +204,6 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
             const bool wave_qbig = __any(qbig);
             commit(0, 0);
             lds_barrier();
-            if (pass == 0) RC_STAMP(2);
 
             for (int jt = 0; jt < n_jt; ++jt) {
                 const int buf = jt & 1;
@@ -280,7 +267,6 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
         }
     }
 
-    RC_STAMP(3);
     // dv partial of this sample: sum dS t = sum dS - 2 sum dS r
     s_dv[w][lane] = (accV[0] + accV[1]) + (accV[2] + accV[3]);
     lds_barrier();
@@ -300,7 +286,6 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
         if (lane == 0) store_agent(&flags[blockIdx.y], epoch);
     }
     if ((int)blockIdx.y != n_slots - 1) return;
-    RC_STAMP(5);
     lds_barrier();                                   // s_dv is reused below
     const long long t_wait0 = wall_clock64();
     int seen = 1;
@@ -341,26 +326,8 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
     }
     // leave the flags cleared: a replay of a captured launch carries the same launch number
     for (int s0 = threadIdx.x; s0 < n_slots; s0 += RC_THREADS) store_agent(&flags[s0], 0ull);
-    RC_STAMP(4);
-#ifdef ECHO_TIMING
-    {
-        const int bid_ = blockIdx.y * gridDim.x + blockIdx.x;
-        if (threadIdx.x == 0 && bid_ < 16384) {
-            unsigned hw, xcc;
-            asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
-            asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-            g_rc_stamps[bid_ * 8 + 7] = ((long long)xcc << 32) | hw;
-            g_rc_stamps[bid_ * 8 + 6] = ((long long)b << 16) | L;
-        }
-    }
-#endif
 }
 
-#ifdef ECHO_TIMING
-extern "C" int echo_debug_stamps_rc(long long *host, int n) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_rc_stamps), (size_t)n * sizeof(long long));
-}
-#endif
 
 template <typename T>
 static hipError_t launch_recompute_t(const AttnShape &s, const void *Qp, const void *Kp, const void *v,
