@@ -40,7 +40,12 @@
  *   - key_len values are clamped, not validated (that would need a sync).
  *   - Results are bit-identical from run to run: no floating-point atomics.
  *   - Calls are re-entrant; calls that share a workspace must be ordered by
- *     the caller (same stream, or events).
+ *     the caller (same stream, or events).  What the library keeps between calls is per host thread and
+ *     never affects results: the text of the thread's last error (echo_last_error_detail), the event records
+ *     of echo_attn_profile_* while profiling is enabled on that thread, a process-wide counter that numbers
+ *     backward launches, and a note per device of kernels whose on-chip memory limit has been raised.
+ *   - A HIP error left pending on the calling thread by earlier, unrelated HIP calls is cleared when a call
+ *     launches a kernel, so that ECHO_ERR_HIP always refers to the library's own launch.
  */
 #ifndef ECHOATTN_H
 #define ECHOATTN_H
@@ -55,7 +60,7 @@ extern "C" {
 typedef enum {
     ECHO_OK = 0,
     ECHO_ERR_NULL = 1,       /* a required pointer is NULL */
-    ECHO_ERR_SHAPE = 2,      /* a dimension is < 1 or a tensor exceeds 2^31-1 elements per sample / 2^62 in total */
+    ECHO_ERR_SHAPE = 2,      /* a shape outside what the library takes, see "Shape limits" below */
     ECHO_ERR_DTYPE = 3,      /* in_dtype is not one of echo_dtype_t */
     ECHO_ERR_WORKSPACE = 4,  /* workspace_bytes smaller than the matching *_workspace_bytes() */
     ECHO_ERR_ALIGN = 5,      /* a device pointer is not 16-byte aligned */
@@ -63,6 +68,21 @@ typedef enum {
 } echo_status_t;
 
 typedef enum { ECHO_F32 = 0, ECHO_BF16 = 1 } echo_dtype_t; /* storage of Qp, Kp, V, v */
+
+/* Shape limits.  Every call returns ECHO_ERR_SHAPE, before anything is launched, unless
+ *   - B, Tq, Tk, H, Dv are all >= 1;
+ *   - Dv is a multiple of 4 (value rows are read 16 bytes at a time);
+ *   - Tk <= ECHO_ATTN_MAX_TK (16 rows of dP over all keys sit in on-chip memory in the softmax backward);
+ *     the echo_attn_step_* calls take Tk <= ECHO_ATTN_STEP_MAX_TK instead;
+ *   - B <= ECHO_ATTN_MAX_B (the batch is one dimension of the launch grid);
+ *   - each per-sample tensor (Tq*H, Tk*H, Tk*Dv, Tq*Dv, Tq*(Tk+16) elements) stays below 2^31 elements and
+ *     B*Tq*Tk*H below 2^62;
+ *   - for the echo_attn_step_* calls, Tq == 1.
+ * H may be any value >= 1: shapes whose H is not a multiple of 4, or whose tile of query rows does not fit
+ * on-chip memory (H above about 4600), run through separate score / softmax / context kernels. */
+#define ECHO_ATTN_MAX_TK 2048
+#define ECHO_ATTN_STEP_MAX_TK 8192
+#define ECHO_ATTN_MAX_B 65535
 
 typedef struct {
     int32_t B;        /* batch                      */
@@ -74,8 +94,11 @@ typedef struct {
 } echo_attn_desc_t;
 
 /* Scratch the two passes need, in bytes (host arithmetic; 0 on an invalid
- * descriptor).  Workspace contents need not survive between calls: the only
- * state that persists from forward to backward is P (Section 5.1). */
+ * descriptor).  Workspace contents need not survive between calls and may start in any state: the only
+ * state that persists from forward to backward is P (Section 5.1).
+ * The forward pass needs none (0 is returned, and echo_attn_fwd then accepts workspace == NULL) whenever its
+ * one-kernel form runs, which keeps the scores on chip: H a multiple of 4 and a tile of eight query rows
+ * within on-chip memory, i.e. every shape of practical size; otherwise B*Tq*Tk floats for the scores. */
 size_t echo_attn_fwd_workspace_bytes(const echo_attn_desc_t *desc);
 size_t echo_attn_bwd_workspace_bytes(const echo_attn_desc_t *desc);
 
@@ -133,7 +156,7 @@ echo_status_t echo_attn_bwd_accumulate(const echo_attn_desc_t *desc,
                                        float *dQp, float *dKp, float *dV, float *dv,
                                        void *workspace, size_t workspace_bytes, void *stream);
 
-/* The same decoder step in one launch per direction (Tq must be 1; Tk <= 8192; no workspace).
+/* The same decoder step in one launch per direction (Tq must be 1; Tk <= ECHO_ATTN_STEP_MAX_TK; no workspace).
  * echo_attn_step_fwd: same results as echo_attn_fwd with Tq = 1 (context [B,1,Dv] and P [B,1,Tk] overwritten).
  * echo_attn_step_bwd: with one query per sample everything but dv
  * is local to a sample, so one kernel takes each sample through dP, the softmax backward, the recomputation of
@@ -142,7 +165,8 @@ echo_status_t echo_attn_bwd_accumulate(const echo_attn_desc_t *desc,
  * sentence.  After the last step echo_attn_step_finish adds the per-sample parts in index order:
  * dv[h] = sum_b dv_part[b,h] (dv is overwritten).  Results equal echo_attn_bwd on the steps stacked along Tq up
  * to the order of additions, and are reproducible for a given order of calls.
- * Errors as echo_attn_bwd; ECHO_ERR_SHAPE also for Tq != 1 or Tk > 8192. */
+ * Errors as echo_attn_bwd; ECHO_ERR_SHAPE also for Tq != 1; the key axis may be as long as
+ * ECHO_ATTN_STEP_MAX_TK. */
 echo_status_t echo_attn_step_fwd(const echo_attn_desc_t *desc,
                                  const void *Qp, const void *Kp, const void *V, const void *v,
                                  const int32_t *key_len, float *context, float *P, void *stream);
@@ -158,6 +182,7 @@ echo_status_t echo_attn_step_finish(const echo_attn_desc_t *desc, const float *d
  * `tanh_map` is B*Tq*Tk*H fp32 (echo_attn_stash_bytes), written by the
  * forward call and read by the backward call in place of the recomputation. */
 size_t echo_attn_stash_bytes(const echo_attn_desc_t *desc);
+size_t echo_attn_fwd_stash_workspace_bytes(const echo_attn_desc_t *desc);   /* workspace of echo_attn_fwd_stash */
 echo_status_t echo_attn_fwd_stash(const echo_attn_desc_t *desc,
                                   const void *Qp, const void *Kp, const void *V, const void *v,
                                   const int32_t *key_len,

@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libechoattn.so")
 
 ECHO_OK, ECHO_ERR_NULL, ECHO_ERR_SHAPE, ECHO_ERR_DTYPE, ECHO_ERR_WORKSPACE, ECHO_ERR_ALIGN, ECHO_ERR_HIP = range(7)
 ECHO_F32, ECHO_BF16 = 0, 1
+ECHO_ATTN_MAX_TK, ECHO_ATTN_STEP_MAX_TK, ECHO_ATTN_MAX_B = 2048, 8192, 65535
 DTYPES = {"f32": ECHO_F32, "bf16": ECHO_BF16}
 
 
@@ -36,6 +37,7 @@ EXPORTS = {
     "echo_attn_fwd_workspace_bytes": (c_size_t, [POINTER(echo_attn_desc_t)]),
     "echo_attn_bwd_workspace_bytes": (c_size_t, [POINTER(echo_attn_desc_t)]),
     "echo_attn_stash_bytes": (c_size_t, [POINTER(echo_attn_desc_t)]),
+    "echo_attn_fwd_stash_workspace_bytes": (c_size_t, [POINTER(echo_attn_desc_t)]),
     "echo_attn_fwd": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 8 + [c_size_t, c_void_p]),
     "echo_attn_bwd": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 12 + [c_size_t, c_void_p]),
     "echo_attn_bwd_static": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 12),
@@ -117,6 +119,10 @@ def echo_attn_fwd_workspace_bytes(desc) -> int:
 
 def echo_attn_bwd_workspace_bytes(desc) -> int:
     return lib().echo_attn_bwd_workspace_bytes(ctypes.byref(desc))
+
+
+def echo_attn_fwd_stash_workspace_bytes(desc) -> int:
+    return lib().echo_attn_fwd_stash_workspace_bytes(ctypes.byref(desc))
 
 
 def echo_attn_stash_bytes(desc) -> int:

@@ -15,17 +15,19 @@ namespace {
 
 using echo::AttnShape;
 
-constexpr int kMaxTk = 2048;   // dP rows of 16 queries live in LDS in the softmax-backward kernel
+constexpr int kMaxTk = ECHO_ATTN_MAX_TK;            // dP rows of 16 queries live in LDS in the softmax-backward kernel
+constexpr int kMaxTkStep = ECHO_ATTN_STEP_MAX_TK;   // one row of scores and one of dS live in LDS in the step kernels
+constexpr int kMaxB = ECHO_ATTN_MAX_B;              // the batch is a grid y dimension
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
-echo_status_t check_desc(const echo_attn_desc_t *d, AttnShape *s) {
+echo_status_t check_desc(const echo_attn_desc_t *d, AttnShape *s, int max_tk = kMaxTk) {
     if (!d) return ECHO_ERR_NULL;
     if (d->in_dtype != ECHO_F32 && d->in_dtype != ECHO_BF16) return ECHO_ERR_DTYPE;
     if (d->B < 1 || d->Tq < 1 || d->Tk < 1 || d->H < 1 || d->Dv < 1) return ECHO_ERR_SHAPE;
     if (d->Dv % 4 != 0) return ECHO_ERR_SHAPE;            // value rows are read 16 bytes at a time
-    if (d->Tk > kMaxTk) return ECHO_ERR_SHAPE;
-    if (d->B > 65535) return ECHO_ERR_SHAPE;              // batch is a grid y/z dimension
+    if (d->Tk > max_tk) return ECHO_ERR_SHAPE;
+    if (d->B > kMaxB) return ECHO_ERR_SHAPE;
     const int64_t lim = (int64_t)1 << 31;
     const int64_t per_sample[] = {(int64_t)d->Tq * d->H, (int64_t)d->Tk * d->H, (int64_t)d->Tk * d->Dv,
                                   (int64_t)d->Tq * d->Dv, (int64_t)d->Tq * (d->Tk + 16)};
@@ -53,7 +55,11 @@ BwdWs bwd_layout(const AttnShape &s) {
     w.total = w.dvflag_off + align_up((size_t)((s.H + 63) / 64) * s.B * sizeof(unsigned long long));
     return w;
 }
-size_t fwd_bytes(const AttnShape &s) { return align_up((size_t)s.B * s.Tq * s.Tk * sizeof(float)); }
+// scores S [B,Tq,Tk] of the unfused forward kernels; the fused kernel keeps them in LDS and needs nothing
+size_t fwd_bytes(const AttnShape &s, bool want_map) {
+    if (!want_map && echo::fwd_fused_supported(s)) return 0;
+    return align_up((size_t)s.B * s.Tq * s.Tk * sizeof(float));
+}
 
 // ---- optional per-kernel timing ------------------------------------------------
 struct ProfRec {
@@ -86,9 +92,12 @@ thread_local std::string g_last_error;
 std::atomic<unsigned long long> g_launch_number{0x9E3779B97F4A7C15ull};
 unsigned long long next_launch_number() { return g_launch_number.fetch_add(2, std::memory_order_relaxed) | 1ull; }
 
+// A HIP error left pending on the calling thread by earlier, unrelated calls is cleared first, so that what
+// is reported belongs to this launch.
 #define ECHO_LAUNCH(NAME, CALL)                                                  \
     do {                                                                         \
         hipError_t e_;                                                           \
+        (void)hipGetLastError();                                                 \
         {                                                                        \
             Timed t_(NAME, st);                                                  \
             e_ = (CALL);                                                         \
@@ -105,12 +114,13 @@ echo_status_t fwd_impl(const echo_attn_desc_t *desc, const void *Qp, const void 
     AttnShape s;
     echo_status_t rc = check_desc(desc, &s);
     if (rc != ECHO_OK) return rc;
-    if (!Qp || !Kp || !V || !v || !key_len || !context || !P || !workspace) return ECHO_ERR_NULL;
+    const size_t need = fwd_bytes(s, want_map);
+    if (!Qp || !Kp || !V || !v || !key_len || !context || !P || (need > 0 && !workspace)) return ECHO_ERR_NULL;
     if (want_map && !tmap) return ECHO_ERR_NULL;
     const void *ptrs[] = {Qp, Kp, V, v, key_len, context, P, workspace, tmap};
     for (const void *p : ptrs)
         if (p && misaligned(p)) return ECHO_ERR_ALIGN;
-    if (workspace_bytes < fwd_bytes(s)) return ECHO_ERR_WORKSPACE;
+    if (workspace_bytes < need) return ECHO_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     float *S = static_cast<float *>(workspace);
     if (!want_map && echo::fwd_fused_supported(s)) {
@@ -190,12 +200,17 @@ extern "C" {
 
 size_t echo_attn_fwd_workspace_bytes(const echo_attn_desc_t *desc) {
     AttnShape s;
-    return check_desc(desc, &s) == ECHO_OK ? fwd_bytes(s) : 0;
+    return check_desc(desc, &s) == ECHO_OK ? fwd_bytes(s, false) : 0;
 }
 
 size_t echo_attn_bwd_workspace_bytes(const echo_attn_desc_t *desc) {
     AttnShape s;
     return check_desc(desc, &s) == ECHO_OK ? bwd_layout(s).total : 0;
+}
+
+size_t echo_attn_fwd_stash_workspace_bytes(const echo_attn_desc_t *desc) {
+    AttnShape s;
+    return check_desc(desc, &s) == ECHO_OK ? fwd_bytes(s, true) : 0;
 }
 
 size_t echo_attn_stash_bytes(const echo_attn_desc_t *desc) {
@@ -248,7 +263,7 @@ echo_status_t echo_attn_bwd_accumulate(const echo_attn_desc_t *desc, const float
 echo_status_t echo_attn_step_fwd(const echo_attn_desc_t *desc, const void *Qp, const void *Kp, const void *V,
                                  const void *v, const int32_t *key_len, float *context, float *P, void *stream) {
     AttnShape s;
-    echo_status_t rc = check_desc(desc, &s);
+    echo_status_t rc = check_desc(desc, &s, kMaxTkStep);
     if (rc != ECHO_OK) return rc;
     if (s.Tq != 1 || echo::step_lds_bytes(s) > 64 * 1024) return ECHO_ERR_SHAPE;
     if (!Qp || !Kp || !V || !v || !key_len || !context || !P) return ECHO_ERR_NULL;
@@ -265,7 +280,7 @@ echo_status_t echo_attn_step_bwd(const echo_attn_desc_t *desc, const float *dCon
                                  const int32_t *key_len, float *dQp, float *dKp, float *dV, float *dv_part,
                                  void *stream) {
     AttnShape s;
-    echo_status_t rc = check_desc(desc, &s);
+    echo_status_t rc = check_desc(desc, &s, kMaxTkStep);
     if (rc != ECHO_OK) return rc;
     if (s.Tq != 1 || echo::step_lds_bytes(s) > 64 * 1024) return ECHO_ERR_SHAPE;
     if (!dContext || !P || !Qp || !Kp || !V || !v || !key_len || !dQp || !dKp || !dV || !dv_part) return ECHO_ERR_NULL;
@@ -279,7 +294,7 @@ echo_status_t echo_attn_step_bwd(const echo_attn_desc_t *desc, const float *dCon
 
 echo_status_t echo_attn_step_finish(const echo_attn_desc_t *desc, const float *dv_part, float *dv, void *stream) {
     AttnShape s;
-    echo_status_t rc = check_desc(desc, &s);
+    echo_status_t rc = check_desc(desc, &s, kMaxTkStep);
     if (rc != ECHO_OK) return rc;
     if (!dv_part || !dv) return ECHO_ERR_NULL;
     if (misaligned(dv_part) || misaligned(dv)) return ECHO_ERR_ALIGN;

@@ -677,9 +677,9 @@ static hipError_t launch_fwd_fused_t(const AttnShape &s, const void *Qp, const v
     const int Hp = (s.H + FW_SS - 1) / FW_SS * FW_SS;
     const int spitch = ((s.Tk + 3) & ~3) + 4;
     const size_t lds = fwd_lds_bytes(s, NG);
-    if (lds > 48 * 1024) {   // beyond the default dynamic LDS limit: raise it (no state is kept between calls)
-        hipError_t e = hipFuncSetAttribute((const void *)k_fwd_fused<T, NG, ROWNS>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (lds > 48 * 1024) {   // beyond the default dynamic LDS limit
+        static LdsGrants granted;
+        hipError_t e = ensure_dynamic_lds((const void *)k_fwd_fused<T, NG, ROWNS>, lds, granted);
         if (e != hipSuccess) return e;
     }
     const int tiles = (s.Tq + RT - 1) / RT;

@@ -409,11 +409,10 @@ hipError_t launch_bwd_pre(const AttnShape &s, const float *dC, const void *V, co
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     const int pitch16 = (s.Tk + 15) / 16 * 16 + 4;
     const size_t lds = (size_t)(s.Tk <= kDsplitMaxTk ? 4 : 1) * 16 * pitch16 * sizeof(float);
-    if (lds > 48 * 1024) {   // beyond the default dynamic LDS limit: raise it (up to 160 KB per block on gfx950)
-        hipError_t e = s.bf16 ? hipFuncSetAttribute((const void *)k_bwd_pre<bf16_t>,
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
-                              : hipFuncSetAttribute((const void *)k_bwd_pre<float>,
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (lds > 48 * 1024) {   // beyond the default dynamic LDS limit (up to 160 KB per block on gfx950)
+        static LdsGrants granted_bf16, granted_f32;
+        hipError_t e = s.bf16 ? ensure_dynamic_lds((const void *)k_bwd_pre<bf16_t>, lds, granted_bf16)
+                              : ensure_dynamic_lds((const void *)k_bwd_pre<float>, lds, granted_f32);
         if (e != hipSuccess) return e;
     }
     if (s.bf16)

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 
+#include <atomic>
+
 namespace echo {
 
 struct AttnShape {
@@ -11,6 +13,23 @@ struct AttnShape {
     bool bf16;   // Qp, Kp, V, v stored as bf16
     bool acc;    // backward: add into dKp, dV, dv instead of overwriting them (per-step decoder form)
 };
+
+// Kernels whose dynamic LDS exceeds the default limit need that limit raised, per device.  `granted` (one table
+// per kernel instantiation, zero-initialised) remembers the largest size already granted on each device, so the
+// runtime is asked once per device and size instead of on every launch.  Safe to call from several threads: at
+// worst two of them ask for the same size.
+constexpr int kMaxDevices = 64;
+struct LdsGrants { std::atomic<size_t> bytes[kMaxDevices]; };
+inline hipError_t ensure_dynamic_lds(const void *kernel, size_t bytes, LdsGrants &granted) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (granted.bytes[dev].load(std::memory_order_acquire) >= bytes) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) granted.bytes[dev].store(bytes, std::memory_order_release);
+    return e;
+}
 
 // Row pitch (floats) of the dS workspace: keys rounded up to the key tile of
 // the recompute kernel, pad entries are written as zeros.

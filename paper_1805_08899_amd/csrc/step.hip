@@ -251,10 +251,9 @@ hipError_t launch_step_fwd(const AttnShape &s, const void *Qp, const void *Kp, c
     const size_t lds = (size_t)s.Tk * sizeof(float);
     if (lds > 64 * 1024) return hipErrorInvalidValue;
     if (lds > 48 * 1024) {
-        hipError_t e = s.bf16 ? hipFuncSetAttribute((const void *)k_step_fwd<bf16_t>,
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
-                              : hipFuncSetAttribute((const void *)k_step_fwd<float>,
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        static LdsGrants granted_bf16, granted_f32;
+        hipError_t e = s.bf16 ? ensure_dynamic_lds((const void *)k_step_fwd<bf16_t>, lds, granted_bf16)
+                              : ensure_dynamic_lds((const void *)k_step_fwd<float>, lds, granted_f32);
         if (e != hipSuccess) return e;
     }
     if (s.bf16)
@@ -274,10 +273,9 @@ hipError_t launch_step_bwd(const AttnShape &s, const float *dC, const float *P, 
     const size_t lds = step_lds_bytes(s);
     if (lds > 64 * 1024) return hipErrorInvalidValue;
     if (lds > 40 * 1024) {
-        hipError_t e = s.bf16 ? hipFuncSetAttribute((const void *)k_step_bwd<bf16_t>,
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
-                              : hipFuncSetAttribute((const void *)k_step_bwd<float>,
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        static LdsGrants granted_bf16, granted_f32;
+        hipError_t e = s.bf16 ? ensure_dynamic_lds((const void *)k_step_bwd<bf16_t>, lds, granted_bf16)
+                              : ensure_dynamic_lds((const void *)k_step_bwd<float>, lds, granted_f32);
         if (e != hipSuccess) return e;
     }
     const int n_hs = (s.H + 63) / 64;

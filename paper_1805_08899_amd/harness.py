@@ -10,11 +10,19 @@ import torch
 from . import binding as eb
 
 
-class DeviceBatch:
-    """Inputs of one workload resident on the GPU plus output/workspace buffers."""
+GUARD_BYTE = 0xA5
 
-    def __init__(self, wl, inputs, device="cuda:0", stash=False):
+
+class DeviceBatch:
+    """Inputs of one workload resident on the GPU plus output/workspace buffers.
+
+    guard_bytes > 0 places every output and the workspace between two guard zones of that many bytes (a
+    multiple of 16) filled with GUARD_BYTE; check_guards() tells whether a call wrote outside its buffers."""
+
+    def __init__(self, wl, inputs, device="cuda:0", stash=False, guard_bytes=0):
         self.wl, self.device = wl, torch.device(device)
+        assert guard_bytes % 16 == 0
+        self.guard_bytes, self._guarded = guard_bytes, []
         self.desc = eb.make_desc(wl.B, wl.Tq, wl.Tk, wl.H, wl.Dv, wl.in_dtype)
         dev = self.device
 
@@ -28,18 +36,46 @@ class DeviceBatch:
         self.key_len = torch.from_numpy(inputs["key_len"]).to(dev)
         self.dC = torch.from_numpy(inputs["dContext"]).to(dev)
         f32 = dict(dtype=torch.float32, device=dev)
-        self.context = torch.empty(wl.B, wl.Tq, wl.Dv, **f32)
-        self.P = torch.empty(wl.B, wl.Tq, wl.Tk, **f32)
-        self.dQp = torch.empty(wl.B, wl.Tq, wl.H, **f32)
-        self.dKp = torch.empty(wl.B, wl.Tk, wl.H, **f32)
-        self.dV = torch.empty(wl.B, wl.Tk, wl.Dv, **f32)
-        self.dv = torch.empty(wl.H, **f32)
+
+        def out(*shape):
+            n = int(np.prod(shape))
+            return self._alloc(n * 4).view(torch.float32)[:n].view(*shape)
+
+        self.context = out(wl.B, wl.Tq, wl.Dv)
+        self.P = out(wl.B, wl.Tq, wl.Tk)
+        self.dQp = out(wl.B, wl.Tq, wl.H)
+        self.dKp = out(wl.B, wl.Tk, wl.H)
+        self.dV = out(wl.B, wl.Tk, wl.Dv)
+        self.dv = out(wl.H)
         self.fwd_ws_bytes = eb.echo_attn_fwd_workspace_bytes(self.desc)
         self.bwd_ws_bytes = eb.echo_attn_bwd_workspace_bytes(self.desc)
-        self.ws = torch.empty(max(self.fwd_ws_bytes, self.bwd_ws_bytes, 16), dtype=torch.uint8, device=dev)
+        if stash:
+            self.fwd_ws_bytes = eb.echo_attn_fwd_stash_workspace_bytes(self.desc)
+        self.ws = self._alloc(max(self.fwd_ws_bytes, self.bwd_ws_bytes, 16))
         self.tanh_map = None
         if stash:
             self.tanh_map = torch.empty(eb.echo_attn_stash_bytes(self.desc) // 4, **f32)
+
+    def _alloc(self, nbytes):
+        """nbytes of uint8 (rounded up to 16) on the device, between guard zones if asked for."""
+        g = self.guard_bytes
+        if g == 0:
+            return torch.empty((nbytes + 15) // 16 * 16, dtype=torch.uint8, device=self.device)
+        # the rear zone starts right at the end of the buffer (at the next multiple of 4 bytes)
+        nbytes = (nbytes + 3) // 4 * 4
+        whole = torch.full((nbytes + 2 * g + 16,), GUARD_BYTE, dtype=torch.uint8, device=self.device)
+        self._guarded.append((whole, nbytes))
+        return whole[g:g + (nbytes + 15) // 16 * 16]
+
+    def check_guards(self):
+        """Names (by allocation order) of the buffers whose guard zones no longer hold GUARD_BYTE."""
+        torch.cuda.synchronize(self.device)
+        g, bad = self.guard_bytes, []
+        for k, (whole, nbytes) in enumerate(self._guarded):
+            ok = bool((whole[:g] == GUARD_BYTE).all()) and bool((whole[g + nbytes:] == GUARD_BYTE).all())
+            if not ok:
+                bad.append(("context", "P", "dQp", "dKp", "dV", "dv", "workspace")[k] if k < 7 else str(k))
+        return bad
 
     def _stream(self):
         return torch.cuda.current_stream(self.device)

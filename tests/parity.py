@@ -19,6 +19,14 @@ def rel_err(got, ref):
     return float(np.abs(got.astype(np.float64) - ref).max() / max(np.abs(ref).max(), 1e-30))
 
 
+def elementwise_err(got, ref):
+    """max_k |got_k - ref_k| / (|ref_k| + 1e-3 max|ref|): information beside the per-tensor figure; it weighs
+    errors at small entries more."""
+    ref = np.asarray(ref, dtype=np.float64)
+    scale = 1e-3 * max(np.abs(ref).max(), 1e-30)
+    return float((np.abs(got.astype(np.float64) - ref) / (np.abs(ref) + scale)).max())
+
+
 def assert_parity(got, ref, inputs, in_dtype, what=""):
     tol = TOL[in_dtype]
     Tk = inputs["Kp"].shape[1]
@@ -27,6 +35,9 @@ def assert_parity(got, ref, inputs, in_dtype, what=""):
         assert got[k].shape == ref[k].shape, (what, k)
         assert np.isfinite(got[k]).all(), f"{what} {k}: non-finite values (unwritten output?)"
         report[k] = rel_err(got[k], ref[k])
+    print(f"{what}: max-abs error / max|ref| per tensor:", {k: f"{e:.2e}" for k, e in report.items()},
+          "| element-wise variant (information):", {k: f"{elementwise_err(got[k], ref[k]):.2e}" for k in KEYS},
+          flush=True)
     bad = {k: e for k, e in report.items() if not e <= tol}
     assert not bad, f"{what}: over tolerance {tol}: {bad} (all: {report})"
     # masked keys: exact zeros, bit for bit

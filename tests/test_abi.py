@@ -63,13 +63,17 @@ def _bwd(desc, **kw):
 
 def test_rejects_bad_arguments_without_launching():
     good = eb.make_desc(4, 6, 7, 16, 16)
-    for name in ("Qp", "Kp", "V", "v", "key_len", "context", "P", "workspace"):
+    for name in ("Qp", "Kp", "V", "v", "key_len", "context", "P"):
         assert _fwd(good, **{name: None}) == eb.ECHO_ERR_NULL, name
+    # H = 18 is not a multiple of 4: the forward pass keeps its scores in the workspace and must be given one
+    unfused = eb.make_desc(4, 6, 7, 18, 16)
+    assert eb.echo_attn_fwd_workspace_bytes(unfused) >= 4 * 6 * 7 * 4
+    assert _fwd(unfused, workspace=None) == eb.ECHO_ERR_NULL
+    assert _fwd(unfused, workspace_bytes=eb.echo_attn_fwd_workspace_bytes(unfused) - 1) == eb.ECHO_ERR_WORKSPACE
     for name in ("dContext", "P", "Qp", "Kp", "V", "v", "key_len", "dQp", "dKp", "dV", "dv", "workspace"):
         assert _bwd(good, **{name: None}) == eb.ECHO_ERR_NULL, name
     assert _fwd(good, Qp=A + 4) == eb.ECHO_ERR_ALIGN
     assert _bwd(good, dKp=A + 8) == eb.ECHO_ERR_ALIGN
-    assert _fwd(good, workspace_bytes=eb.echo_attn_fwd_workspace_bytes(good) - 1) == eb.ECHO_ERR_WORKSPACE
     assert _bwd(good, workspace_bytes=eb.echo_attn_bwd_workspace_bytes(good) - 1) == eb.ECHO_ERR_WORKSPACE
     for field in ("B", "Tq", "Tk", "H", "Dv"):
         for val in (0, -3):
@@ -79,6 +83,45 @@ def test_rejects_bad_arguments_without_launching():
     assert _fwd(eb.make_desc(4, 6, 7, 16, 18)) == eb.ECHO_ERR_SHAPE          # Dv not a multiple of 4
     assert _fwd(eb.make_desc(1, 70000, 70, 70000, 16)) == eb.ECHO_ERR_SHAPE  # per-sample tensor >= 2^31 elements
     assert _fwd(eb.make_desc(4, 6, 7, 16, 16, in_dtype=7)) == eb.ECHO_ERR_DTYPE
+
+
+def test_one_kernel_forward_needs_no_workspace():
+    """Shapes that take the one-kernel forward report 0 bytes; the keep-the-map variant still needs the scores."""
+    for shape in ((4, 6, 7, 16, 16), (64, 50, 50, 512, 512), (32, 300, 300, 1024, 1024), (2, 9, 64, 2048, 64)):
+        d = eb.make_desc(*shape)
+        assert eb.echo_attn_fwd_workspace_bytes(d) == 0, shape
+        assert eb.echo_attn_fwd_stash_workspace_bytes(d) >= shape[0] * shape[1] * shape[2] * 4, shape
+    d = eb.make_desc(4, 6, 7, 16, 16)
+    assert eb.echo_attn_fwd_stash(d, A, A, A, A, A, A, A, A, None, 0) == eb.ECHO_ERR_NULL
+    assert eb.echo_attn_fwd_stash(d, A, A, A, A, A, A, A, A, A, 16) == eb.ECHO_ERR_WORKSPACE
+
+
+def test_documented_shape_limits():
+    """Each limit of the header's "Shape limits", at the first value past it and (host checks only) at the last one
+    inside, through a call that stops at the next check (a NULL tensor) instead of launching."""
+    def fwd_rc(*shape):
+        return _fwd(eb.make_desc(*shape), Qp=None)
+
+    def bwd_rc(*shape):
+        return _bwd(eb.make_desc(*shape), dContext=None)
+    assert eb.ECHO_ATTN_MAX_TK == 2048 and eb.ECHO_ATTN_STEP_MAX_TK == 8192 and eb.ECHO_ATTN_MAX_B == 65535
+    for rc in (fwd_rc, bwd_rc):
+        assert rc(2, 3, eb.ECHO_ATTN_MAX_TK, 8, 8) == eb.ECHO_ERR_NULL
+        assert rc(2, 3, eb.ECHO_ATTN_MAX_TK + 1, 8, 8) == eb.ECHO_ERR_SHAPE
+        assert rc(eb.ECHO_ATTN_MAX_B, 3, 5, 8, 8) == eb.ECHO_ERR_NULL
+        assert rc(eb.ECHO_ATTN_MAX_B + 1, 3, 5, 8, 8) == eb.ECHO_ERR_SHAPE
+        for dv in (1, 2, 3, 6, 18):
+            assert rc(2, 3, 5, 8, dv) == eb.ECHO_ERR_SHAPE, dv
+        assert rc(2, 3, 5, 7, 4) == eb.ECHO_ERR_NULL                   # any H >= 1
+    big = eb.make_desc(eb.ECHO_ATTN_MAX_B + 1, 3, 5, 8, 8)
+    assert eb.echo_attn_fwd_workspace_bytes(big) == 0 and eb.echo_attn_bwd_workspace_bytes(big) == 0
+    assert eb.echo_attn_bwd_static(big, A, A, A, A, A, A, A, A, A, A, A) == eb.ECHO_ERR_SHAPE
+    # the step calls take a longer key axis
+    step = lambda tk: eb.echo_attn_step_fwd(eb.make_desc(2, 1, tk, 8, 8), None, A, A, A, A, A, A)
+    assert step(eb.ECHO_ATTN_MAX_TK + 1) == eb.ECHO_ERR_NULL
+    assert step(eb.ECHO_ATTN_STEP_MAX_TK) == eb.ECHO_ERR_NULL
+    assert step(eb.ECHO_ATTN_STEP_MAX_TK + 1) == eb.ECHO_ERR_SHAPE
+    assert eb.echo_attn_step_finish(eb.make_desc(2, 1, eb.ECHO_ATTN_STEP_MAX_TK + 1, 8, 8), A, A) == eb.ECHO_ERR_SHAPE
 
 
 def test_null_descriptor():

@@ -70,6 +70,19 @@ EDGE = [
     ("fused_forward_one_key", 3, 5, 1, 32, 4, "f32", [1, 1, 1]),
     ("fused_forward_two_keys", 2, 9, 2, 64, 8, "f32", [2, 2]),
     ("fused_forward_three_keys", 2, 9, 3, 260, 8, "f32", [3, 3]),
+    # one-kernel forward whose row tile needs more LDS than the default limit (the limit is raised once per device)
+    ("fused_forward_lds_beyond_default", 2, 9, 64, 2048, 64, "f32", None),
+    # row tile beyond on-chip memory: the forward falls back to the score / softmax / context kernels
+    ("forward_fallback_at_large_h", 2, 5, 9, 4864, 8, "f32", None),
+    # placement by rank at batch sizes that do not fill the XCDs evenly
+    ("ranked_placement_b47", 47, 9, 12, 64, 8, "f32", None),
+    ("ranked_placement_b100", 100, 3, 20, 32, 4, "f32", None),
+    ("ranked_placement_b127", 127, 2, 7, 16, 4, "f32", None),
+    # row mode of the forward kernel at 2 and 4 slices of h, longest key shares, and streaming mode right past them
+    ("row_mode_two_slices_eight_keys_per_wave", 2, 11, 64, 512, 16, "f32", [64, 37]),
+    ("row_mode_four_slices", 2, 10, 32, 1024, 16, "f32", [32, 5]),
+    ("row_mode_bf16_four_slices", 2, 9, 30, 900, 16, "bf16", None),
+    ("streaming_mode_just_past_row_mode", 2, 11, 65, 512, 16, "f32", [65, 64]),
 ]
 
 
@@ -84,6 +97,78 @@ def test_edge_shapes(H, case):
     _, got = run_gpu(H, wl, inputs)
     ref = oracle_outputs(inputs, workers=1)
     assert_parity(got, ref, inputs, dt, name)
+
+
+GUARDED = [
+    # name, B, Tq, Tk, H, Dv, dtype, stash
+    ("guard_tiny", 4, 6, 7, 16, 16, "f32", False),
+    ("guard_ragged", 3, 37, 45, 200, 36, "f32", False),
+    ("guard_unfused_forward", 2, 19, 23, 70, 12, "f32", False),
+    ("guard_bf16", 3, 21, 34, 130, 20, "bf16", False),
+    ("guard_long_keys", 1, 9, 300, 64, 8, "f32", False),
+    ("guard_stash", 4, 6, 7, 16, 16, "f32", True),
+]
+
+
+@pytest.mark.parametrize("case", GUARDED, ids=[c[0] for c in GUARDED])
+def test_no_write_outside_the_buffers(H, case):
+    """Every output and the workspace sit between 4 KB guard zones holding a pattern; after forward + backward
+    (and the no-workspace backward) the zones must be untouched."""
+    import torch
+    from paper_1805_08899_amd import binding as eb
+    name, B, Tq, Tk, Hh, Dv, dt, stash = case
+    print("guarded case", case, flush=True)
+    wl = Workload(name, B, Tq, Tk, Hh, Dv, dt, 0.5, 1, Tk, dt == "bf16")
+    inputs = make_inputs(wl, seed=808 + len(name))
+    db = H.DeviceBatch(wl, inputs, stash=stash, guard_bytes=4096)
+    db.poison_outputs()
+    if stash:
+        db.fwd_stash(); db.bwd_stash()
+    else:
+        db.fwd(); db.bwd()
+    assert db.check_guards() == []
+    got = db.results()
+    assert_parity(got, oracle_outputs(inputs, workers=1), inputs, dt, name)
+    if not stash:
+        eb.check(eb.echo_attn_bwd_static(db.desc, db.dC, db.P, db.Qp, db.Kp, db.V, db.v, db.key_len, db.dQp, db.dKp,
+                                         db.dV, db.dv, stream=torch.cuda.current_stream(db.device)), "bwd_static")
+        assert db.check_guards() == []
+
+
+def test_guard_zones_notice_a_stray_write(H):
+    """The checker itself: one byte written just past a buffer, or just before it, is reported."""
+    import torch
+    wl = Workload("guard_self_check", 2, 3, 5, 8, 4, "f32", 0.5, 1, 5)
+    db = H.DeviceBatch(wl, make_inputs(wl, seed=1), guard_bytes=4096)
+    assert db.check_guards() == []
+    whole, nbytes = db._guarded[1]                       # P
+    whole[4096 + nbytes] = 0
+    assert db.check_guards() == ["P"]
+    whole[4096 + nbytes] = H.GUARD_BYTE
+    whole_ws, _ = db._guarded[6]
+    whole_ws[4095] = 0
+    assert db.check_guards() == ["workspace"]
+
+
+def test_no_write_outside_the_buffers_in_the_step_calls(H):
+    """The per-step entry points with guard zones round their outputs."""
+    import torch
+    from paper_1805_08899_amd import binding as eb
+    B, Tk, Hh, Dv = 5, 21, 70, 36
+    wl = Workload("guard_steps", B, 1, Tk, Hh, Dv, "f32", 0.5, 1, Tk)
+    inputs = make_inputs(wl, seed=909)
+    db = H.DeviceBatch(wl, inputs, guard_bytes=4096)
+    dvp = db._alloc(B * Hh * 4).view(torch.float32)[:B * Hh].view(B, Hh)
+    st = torch.cuda.current_stream(db.device)
+    for t in (db.dKp, db.dV, db.dv, dvp):
+        t.zero_()
+    eb.check(eb.echo_attn_step_fwd(db.desc, db.Qp, db.Kp, db.V, db.v, db.key_len, db.context, db.P, stream=st))
+    eb.check(eb.echo_attn_step_bwd(db.desc, db.dC, db.P, db.Qp, db.Kp, db.V, db.v, db.key_len, db.dQp, db.dKp, db.dV,
+                                   dvp, stream=st))
+    eb.check(eb.echo_attn_step_finish(db.desc, dvp, db.dv, stream=st))
+    eb.check(eb.echo_attn_bwd_accumulate(db.desc, db.dC, db.P, db.Qp, db.Kp, db.V, db.v, db.key_len, db.dQp, db.dKp,
+                                         db.dV, db.dv, db.ws, stream=st))
+    assert db.check_guards() == []
 
 
 def test_large_preactivations_take_the_exact_path(H):
@@ -132,6 +217,24 @@ def test_forward_only_and_backward_from_given_P(H):
     db.bwd()
     got = db.results()
     for k in ("dQp", "dKp", "dV", "dv"):
+        assert rel_err(got[k], ref[k]) <= 1e-4, k
+
+
+def test_forward_alone_without_a_workspace(H):
+    """A forward-only caller of a shape that takes the one-kernel forward allocates nothing: 0 bytes are asked
+    for and workspace = NULL is accepted."""
+    import torch
+    from paper_1805_08899_amd import binding as eb
+    wl = WORKLOADS[0]
+    inputs = make_inputs(wl, seed=6)
+    ref = oracle_outputs(inputs, workers=1)
+    db = H.DeviceBatch(wl, inputs)
+    assert eb.echo_attn_fwd_workspace_bytes(db.desc) == 0
+    db.poison_outputs()
+    eb.check(eb.echo_attn_fwd(db.desc, db.Qp, db.Kp, db.V, db.v, db.key_len, db.context, db.P, None, 0,
+                              stream=torch.cuda.current_stream(db.device)), "echo_attn_fwd without workspace")
+    got = db.results()
+    for k in ("context", "P"):
         assert rel_err(got[k], ref[k]) <= 1e-4, k
 
 
