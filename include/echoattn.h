@@ -177,6 +177,33 @@ echo_status_t echo_attn_step_bwd(const echo_attn_desc_t *desc,
                                  float *dQp, float *dKp, float *dV, float *dv_part, void *stream);
 echo_status_t echo_attn_step_finish(const echo_attn_desc_t *desc, const float *dv_part, float *dv, void *stream);
 
+/* Decoder steps with the key-side gradients left to the end of the sentence.  Only dQp of step t is needed before
+ * step t - 1 can run (Section 2: the query of a step comes from the decoder state of that step); dKp, dV and dv
+ * are sums over all steps (Kp, V and v are shared by them), so nothing forces the steps to add to them one by
+ * one: that costs a read and a write of all of dKp and dV per step.  Instead
+ *   echo_attn_step_bwd_query   (once per step, any order) forms that step's dP and dS (Eq. 2, softmax backward),
+ *       re-evaluates tanh (Section 3.4) and writes dQp [B,1,H]; it also leaves the step's row of dS and its sum in
+ *       `ds_rows`, a device buffer of echo_attn_steps_ds_bytes(sentence descriptor) bytes that the caller keeps
+ *       for the sentence (any initial state).  It reads Kp and V once and writes nothing else.  `desc` has
+ *       Tq == 1; `step` in [0, steps) is the position of this step in the stacked tensors below.
+ *   echo_attn_steps_bwd_keys   (once per sentence, after all steps) forms dKp [B,Tk,H], dV [B,Tk,Dv] and dv [H]
+ *       (overwritten) from the steps stacked along Tq: dContext [B,steps,Dv], P [B,steps,Tk], Qp [B,steps,H], and
+ *       `ds_rows` as the steps left it.  `desc` has Tq == steps.  Workspace: echo_attn_bwd_workspace_bytes(desc).
+ * Results equal echo_attn_bwd on the stacked steps up to the order of additions and are reproducible.
+ * Errors as echo_attn_bwd; ECHO_ERR_SHAPE also for Tq != 1 in the step call or step outside [0, steps). */
+size_t echo_attn_steps_ds_bytes(const echo_attn_desc_t *sentence_desc);
+echo_status_t echo_attn_step_bwd_query(const echo_attn_desc_t *desc, int32_t step, int32_t steps,
+                                       const float *dContext, const float *P,
+                                       const void *Qp, const void *Kp, const void *V, const void *v,
+                                       const int32_t *key_len,
+                                       float *dQp, void *ds_rows, void *stream);
+echo_status_t echo_attn_steps_bwd_keys(const echo_attn_desc_t *desc,
+                                       const float *dContext, const float *P,
+                                       const void *Qp, const void *Kp, const void *v,
+                                       const int32_t *key_len, const void *ds_rows,
+                                       float *dKp, float *dV, float *dv,
+                                       void *workspace, size_t workspace_bytes, void *stream);
+
 /* Comparison only: the baseline behaviour of Section 4.1, which stashes the
  * output of tanh as a feature map.  Same results as the pair above;
  * `tanh_map` is B*Tq*Tk*H fp32 (echo_attn_stash_bytes), written by the

@@ -45,6 +45,9 @@ EXPORTS = {
     "echo_attn_step_fwd": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 8),
     "echo_attn_step_bwd": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 12),
     "echo_attn_step_finish": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 3),
+    "echo_attn_steps_ds_bytes": (c_size_t, [POINTER(echo_attn_desc_t)]),
+    "echo_attn_step_bwd_query": (c_int, [POINTER(echo_attn_desc_t), c_int32, c_int32] + [c_void_p] * 10),
+    "echo_attn_steps_bwd_keys": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 11 + [c_size_t, c_void_p]),
     "echo_attn_fwd_stash": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 9 + [c_size_t, c_void_p]),
     "echo_attn_bwd_stash": (c_int, [POINTER(echo_attn_desc_t)] + [c_void_p] * 11 + [c_size_t, c_void_p]),
     "echo_attn_profile_enable": (None, [c_int]),
@@ -178,6 +181,22 @@ def echo_attn_step_bwd(desc, dContext, P, Qp, Kp, V, v, key_len, dQp, dKp, dV, d
 
 def echo_attn_step_finish(desc, dv_part, dv, stream=None) -> int:
     return lib().echo_attn_step_finish(ctypes.byref(desc), _ptr(dv_part), _ptr(dv), _stream(stream))
+
+
+def echo_attn_steps_ds_bytes(desc) -> int:
+    return lib().echo_attn_steps_ds_bytes(ctypes.byref(desc))
+
+
+def echo_attn_step_bwd_query(desc, step, steps, dContext, P, Qp, Kp, V, v, key_len, dQp, ds_rows, stream=None) -> int:
+    return lib().echo_attn_step_bwd_query(ctypes.byref(desc), step, steps, _ptr(dContext), _ptr(P), _ptr(Qp), _ptr(Kp),
+                                          _ptr(V), _ptr(v), _ptr(key_len), _ptr(dQp), _ptr(ds_rows), _stream(stream))
+
+
+def echo_attn_steps_bwd_keys(desc, dContext, P, Qp, Kp, v, key_len, ds_rows, dKp, dV, dv, workspace,
+                             workspace_bytes=None, stream=None) -> int:
+    return lib().echo_attn_steps_bwd_keys(ctypes.byref(desc), _ptr(dContext), _ptr(P), _ptr(Qp), _ptr(Kp), _ptr(v),
+                                          _ptr(key_len), _ptr(ds_rows), _ptr(dKp), _ptr(dV), _ptr(dv), _ptr(workspace),
+                                          _ws_bytes(workspace, workspace_bytes), _stream(stream))
 
 
 def echo_attn_fwd_stash(desc, Qp, Kp, V, v, key_len, context, P, tanh_map, workspace, workspace_bytes=None,

@@ -292,6 +292,62 @@ echo_status_t echo_attn_step_bwd(const echo_attn_desc_t *desc, const float *dCon
     return ECHO_OK;
 }
 
+size_t echo_attn_steps_ds_bytes(const echo_attn_desc_t *desc) {
+    AttnShape s;
+    if (check_desc(desc, &s) != ECHO_OK) return 0;
+    return align_up((size_t)s.B * s.Tq * echo::ds_pitch(s.Tk) * sizeof(float)) + align_up((size_t)s.B * s.Tq * sizeof(float));
+}
+
+echo_status_t echo_attn_step_bwd_query(const echo_attn_desc_t *desc, int32_t step, int32_t steps,
+                                       const float *dContext, const float *P, const void *Qp, const void *Kp,
+                                       const void *V, const void *v, const int32_t *key_len, float *dQp,
+                                       void *ds_rows, void *stream) {
+    AttnShape s;
+    echo_status_t rc = check_desc(desc, &s);
+    if (rc != ECHO_OK) return rc;
+    if (s.Tq != 1 || steps < 1 || step < 0 || step >= steps) return ECHO_ERR_SHAPE;
+    if ((int64_t)steps * (s.Tk + 16) >= ((int64_t)1 << 31)) return ECHO_ERR_SHAPE;
+    if (!dContext || !P || !Qp || !Kp || !V || !v || !key_len || !dQp || !ds_rows) return ECHO_ERR_NULL;
+    const void *ptrs[] = {dContext, P, Qp, Kp, V, v, key_len, dQp, ds_rows};
+    for (const void *p : ptrs)
+        if (misaligned(p)) return ECHO_ERR_ALIGN;
+    float *ds = static_cast<float *>(ds_rows);
+    float *ds_sum = reinterpret_cast<float *>(static_cast<char *>(ds_rows) +
+                                              align_up((size_t)s.B * steps * echo::ds_pitch(s.Tk) * sizeof(float)));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ECHO_LAUNCH("step_bwd_query",
+                echo::launch_step_bwd_query(s, dContext, P, Qp, Kp, V, v, key_len, dQp, ds, ds_sum, steps, step, st));
+    return ECHO_OK;
+}
+
+echo_status_t echo_attn_steps_bwd_keys(const echo_attn_desc_t *desc, const float *dContext, const float *P,
+                                       const void *Qp, const void *Kp, const void *v, const int32_t *key_len,
+                                       const void *ds_rows, float *dKp, float *dV, float *dv, void *workspace,
+                                       size_t workspace_bytes, void *stream) {
+    AttnShape s;
+    echo_status_t rc = check_desc(desc, &s);
+    if (rc != ECHO_OK) return rc;
+    if (!dContext || !P || !Qp || !Kp || !v || !key_len || !ds_rows || !dKp || !dV || !dv || !workspace) return ECHO_ERR_NULL;
+    const void *ptrs[] = {dContext, P, Qp, Kp, v, key_len, ds_rows, dKp, dV, dv, workspace};
+    for (const void *p : ptrs)
+        if (misaligned(p)) return ECHO_ERR_ALIGN;
+    const BwdWs lay = bwd_layout(s);
+    if (workspace_bytes < lay.total) return ECHO_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    // dS and its row sums were left by the steps; the call's own workspace holds the rest
+    float *dS = const_cast<float *>(static_cast<const float *>(ds_rows));
+    float *rowsum = reinterpret_cast<float *>(const_cast<char *>(static_cast<const char *>(ds_rows)) +
+                                              align_up((size_t)s.B * s.Tq * echo::ds_pitch(s.Tk) * sizeof(float)));
+    float *dv_part = reinterpret_cast<float *>(ws + lay.dvpart_off);
+    int *order = reinterpret_cast<int *>(ws + lay.order_off);
+    unsigned long long *dv_flag = reinterpret_cast<unsigned long long *>(ws + lay.dvflag_off);
+    ECHO_LAUNCH("bwd_pre_dv", echo::launch_bwd_pre(s, dContext, nullptr, P, key_len, dS, rowsum, order, dV, st, false));
+    ECHO_LAUNCH("recompute_keys", echo::launch_recompute(s, Qp, Kp, v, order, dS, rowsum, nullptr, nullptr, dKp, dv_part,
+                                                         dv_flag, next_launch_number(), dv, st));
+    return ECHO_OK;
+}
+
 echo_status_t echo_attn_step_finish(const echo_attn_desc_t *desc, const float *dv_part, float *dv, void *stream) {
     AttnShape s;
     echo_status_t rc = check_desc(desc, &s, kMaxTkStep);

@@ -399,11 +399,11 @@ __global__ __launch_bounds__(256, 3) void k_bwd_pre(const float *__restrict__ dC
 }
 
 hipError_t launch_bwd_pre(const AttnShape &s, const float *dC, const void *V, const float *P, const int *key_len,
-                          float *dS, float *ds_rowsum, int *order, float *dV, hipStream_t st) {
+                          float *dS, float *ds_rowsum, int *order, float *dV, hipStream_t st, bool with_ds) {
     const int sorted = s.B <= kMaxSortedB ? 1 : 0;
     const int n_hs = (s.H + 63) / 64;
     const int fold = (sorted && (long long)s.B * n_hs <= 512) ? 1 : 0;   // recompute grid in one round
-    const int s_tiles = (s.Tq + 15) / 16;
+    const int s_tiles = with_ds ? (s.Tq + 15) / 16 : 0;
     const int v_xt = (s.Dv + 255) / 256, v_yt = (s.Tk + 15) / 16;
     const long long blocks = 1 + 8LL * ((s.B + 7) / 8) * (s_tiles + (long long)v_xt * v_yt);
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;

@@ -53,12 +53,13 @@ hipError_t launch_context(const AttnShape &s, const float *P, const void *V, con
 //   ds_rowsum[b*Tq+i] = sum_j dS;
 //   order[r] = b | L_b << 16 for the sample with the r-th most valid keys (index order if B > kMaxSortedB)
 constexpr int kMaxSortedB = 1024;
+// with_ds = false leaves dS and ds_rowsum alone (they are given) and launches only the dV and ranking blocks
 hipError_t launch_bwd_pre(const AttnShape &s, const float *dC, const void *V, const float *P, const int *key_len,
-                          float *dS, float *ds_rowsum, int *order, float *dV, hipStream_t st);
+                          float *dS, float *ds_rowsum, int *order, float *dV, hipStream_t st, bool with_ds = true);
 // B3 + B4  fused recompute: dQp, dKp, per-sample partials of dv (dv_part [B,H]) and, by the blocks that start
 // last, dv[h] = sum_b dv_part[b,h] in index order (added to dv if s.acc).  dv_flag: ceil(H/64) x B words of
 // workspace in any state; epoch: a number no earlier launch on this workspace used (never 0).
-// tmap != nullptr reads tanh from the stashed map instead of recomputing it
+// tmap != nullptr reads tanh from the stashed map instead of recomputing it; dQp == nullptr: dQp is not wanted
 hipError_t launch_recompute(const AttnShape &s, const void *Qp, const void *Kp, const void *v, const int *order,
                             const float *dS, const float *ds_rowsum, const float *tmap, float *dQp, float *dKp,
                             float *dv_part, unsigned long long *dv_flag, unsigned long long epoch, float *dv,
@@ -72,5 +73,11 @@ hipError_t launch_step_fwd(const AttnShape &s, const void *Qp, const void *Kp, c
 hipError_t launch_step_bwd(const AttnShape &s, const float *dC, const float *P, const void *Qp, const void *Kp,
                            const void *V, const void *v, const int *key_len, float *dQp, float *dKp, float *dV,
                            float *dv_part, hipStream_t st);
+
+// The same step with the key-side sums deferred: writes dQp [B,1,H], row `step` of every sample's `steps` rows of
+// dS (ds_out [B, steps, ds_pitch(Tk)]) and that row's sum (ds_sum_out [B, steps]); reads only.
+hipError_t launch_step_bwd_query(const AttnShape &s, const float *dC, const float *P, const void *Qp, const void *Kp,
+                                 const void *V, const void *v, const int *key_len, float *dQp, float *ds_out,
+                                 float *ds_sum_out, int steps, int step, hipStream_t st);
 
 }  // namespace echo

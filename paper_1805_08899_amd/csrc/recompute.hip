@@ -132,14 +132,14 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
     const float vh = hv ? ld(v, hc) : 0.f;
     const float v4 = 4.f * vh;
 
-    float *dQb = dQp + (size_t)b * Tq * H;
+    float *dQb = dQp ? dQp + (size_t)b * Tq * H : nullptr;
     float *dKb = dKp + (size_t)b * Tk * H;
 
     // masked keys: exact zeros (when adding to earlier decoder steps they hold zeros already)
     if (!acc)
         for (int j = L + w; j < Tk; j += RC_W)
             if (hv) dKb[(size_t)j * H + h] = 0.f;
-    if (L == 0) {                                   // block-uniform
+    if (L == 0 && dQp) {                            // block-uniform
         for (int i = w; i < Tq; i += RC_W)
             if (hv) dQb[(size_t)i * H + h] = 0.f;
     }
@@ -258,7 +258,7 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
                     else *dst = *dst + val;
                 }
             }
-            if (hv) {
+            if (hv && dQp) {
 #pragma unroll
                 for (int a = 0; a < RC_RI; ++a)
                     if (a < ni) store_streaming(&dQb[(size_t)(i0 + a) * H + h], v4 * accQ[a]);

@@ -26,11 +26,17 @@ constexpr int ST_KB = 4;                  // keys per wave and batch: a batch of
 // keys 32 n + 4 w .. + 3 of every batch n; the first batch's K, old dKp and old dV are requested before dP is
 // formed.  dP is formed by every h slice of a sample for itself (a few ten thousand multiply-adds, V comes from
 // the L2 that the slices of a sample share).
-template <typename T>
+//
+// DEFER: the key-side sums are left to one batched call at the end of the sentence.  The step then only reads: it
+// writes dQp, and the block of the first h slice writes the step's row of dS (row `ds_row` of the sample's
+// `ds_rows` rows of `ds_pitch` floats, zeros at masked keys and pads) and its sum; dKp, dV and dv_part are not
+// touched.
+template <typename T, bool DEFER>
 __global__ __launch_bounds__(ST_THREADS) void k_step_bwd(
     const float *__restrict__ dC, const float *__restrict__ P, const T *__restrict__ Qp, const T *__restrict__ Kp,
     const T *__restrict__ V, const T *__restrict__ v, const int *__restrict__ key_len, float *__restrict__ dQp,
-    float *__restrict__ dKp, float *__restrict__ dV, float *__restrict__ dv_part, int Tk, int H, int Dv, int cw) {
+    float *__restrict__ dKp, float *__restrict__ dV, float *__restrict__ dv_part, float *__restrict__ ds_out,
+    float *__restrict__ ds_sum_out, int ds_rows, int ds_row, int ds_pitch, int Tk, int H, int Dv, int cw) {
     extern __shared__ float s_step[];     // [Tk] P, then [Tk] dP
     float *s_p = s_step, *s_dp = s_step + Tk;
     __shared__ float s_q[ST_W][64], s_r[ST_W][64];
@@ -40,6 +46,11 @@ __global__ __launch_bounds__(ST_THREADS) void k_step_bwd(
     const bool hv = h < H;
     const int hc = hv ? h : H - 1;
     const int L = clamp_len(key_len[b], Tk);
+    float *ds_dst = DEFER ? ds_out + ((size_t)b * ds_rows + ds_row) * ds_pitch : nullptr;
+    if (DEFER && hs == 0) {               // masked keys and pads of the stored dS row: zeros
+        for (int j = L + (int)threadIdx.x; j < ds_pitch; j += ST_THREADS) ds_dst[j] = 0.f;
+        if (L == 0 && threadIdx.x == 0) ds_sum_out[(size_t)b * ds_rows + ds_row] = 0.f;
+    }
     if (L == 0) {                         // no valid key: the query gets no gradient, the sums get nothing
         if (w == 0 && hv) dQp[(size_t)b * H + h] = 0.f;
         return;
@@ -60,8 +71,8 @@ __global__ __launch_bounds__(ST_THREADS) void k_step_bwd(
     for (int u = 0; u < ST_KB; ++u) {
         const int j = min(ST_KB * w + u, L - 1);
         k0[u] = ld(Kb, (size_t)j * H + hc);
-        oldk0[u] = dKb[(size_t)j * H + hc];
-        oldv0[u] = dVb[(size_t)j * Dv + c0];
+        oldk0[u] = DEFER ? 0.f : dKb[(size_t)j * H + hc];
+        oldv0[u] = DEFER ? 0.f : dVb[(size_t)j * Dv + c0];
     }
     const float sq = kTwoLog2e * ld(Qp, (size_t)b * H + hc);
     const float v4 = hv ? 4.f * ld(v, (size_t)hc) : 0.f;
@@ -112,7 +123,7 @@ __global__ __launch_bounds__(ST_THREADS) void k_step_bwd(
             } else {
                 const size_t at = (size_t)min(j0 + u, L - 1) * H + hc;
                 k[u] = ld(Kb, at);
-                oldk[u] = dKb[at];
+                oldk[u] = DEFER ? 0.f : dKb[at];
             }
         }
 #pragma unroll
@@ -123,10 +134,11 @@ __global__ __launch_bounds__(ST_THREADS) void k_step_bwd(
                 const float g = ds * __builtin_fmaf(-rr, rr, rr);
                 accQ += g;
                 accR = __builtin_fmaf(ds, rr, accR);
-                if (hv) store_streaming(&dKb[(size_t)(j0 + u) * H + h], __builtin_fmaf(v4, g, oldk[u]));
+                if (!DEFER && hv) store_streaming(&dKb[(size_t)(j0 + u) * H + h], __builtin_fmaf(v4, g, oldk[u]));
+                if (DEFER && hs == 0 && lane == 0) ds_dst[j0 + u] = ds;
             }
         }
-        for (int c = c_lo + lane, m = 0; c < c_hi; c += 64, ++m) {
+        for (int c = c_lo + lane, m = 0; !DEFER && c < c_hi; c += 64, ++m) {
             const float dc = dCb[c];
 #pragma unroll
             for (int u = 0; u < ST_KB; ++u) {
@@ -149,8 +161,12 @@ __global__ __launch_bounds__(ST_THREADS) void k_step_bwd(
             tr += s_r[k2][lane];
         }
         store_streaming(&dQp[(size_t)b * H + h], v4 * tq);
-        float *dvp = dv_part + (size_t)b * H + h;
-        *dvp += __builtin_fmaf(-2.f, tr, dsum);
+        if (!DEFER) {
+            float *dvp = dv_part + (size_t)b * H + h;
+            *dvp += __builtin_fmaf(-2.f, tr, dsum);
+        } else if (hs == 0 && lane == 0) {
+            ds_sum_out[(size_t)b * ds_rows + ds_row] = dsum;
+        }
     }
 }
 
@@ -267,29 +283,44 @@ hipError_t launch_step_fwd(const AttnShape &s, const void *Qp, const void *Kp, c
 
 size_t step_lds_bytes(const AttnShape &s) { return 2 * (size_t)s.Tk * sizeof(float); }
 
-hipError_t launch_step_bwd(const AttnShape &s, const float *dC, const float *P, const void *Qp, const void *Kp,
-                           const void *V, const void *v, const int *key_len, float *dQp, float *dKp, float *dV,
-                           float *dv_part, hipStream_t st) {
+template <typename T, bool DEFER>
+static hipError_t launch_step_bwd_t(const AttnShape &s, const float *dC, const float *P, const void *Qp,
+                                    const void *Kp, const void *V, const void *v, const int *key_len, float *dQp,
+                                    float *dKp, float *dV, float *dv_part, float *ds_out, float *ds_sum_out,
+                                    int ds_rows, int ds_row, hipStream_t st) {
     const size_t lds = step_lds_bytes(s);
     if (lds > 64 * 1024) return hipErrorInvalidValue;
     if (lds > 40 * 1024) {
-        static LdsGrants granted_bf16, granted_f32;
-        hipError_t e = s.bf16 ? ensure_dynamic_lds((const void *)k_step_bwd<bf16_t>, lds, granted_bf16)
-                              : ensure_dynamic_lds((const void *)k_step_bwd<float>, lds, granted_f32);
+        static LdsGrants granted;
+        hipError_t e = ensure_dynamic_lds((const void *)k_step_bwd<T, DEFER>, lds, granted);
         if (e != hipSuccess) return e;
     }
     const int n_hs = (s.H + 63) / 64;
     const int cw = (s.Dv + n_hs - 1) / n_hs;                     // columns of dV per h slice
     dim3 grid(n_hs, s.B);
-    if (s.bf16)
-        k_step_bwd<bf16_t><<<grid, ST_THREADS, lds, st>>>(dC, P, (const bf16_t *)Qp, (const bf16_t *)Kp,
-                                                          (const bf16_t *)V, (const bf16_t *)v, key_len, dQp, dKp, dV,
-                                                          dv_part, s.Tk, s.H, s.Dv, cw);
-    else
-        k_step_bwd<float><<<grid, ST_THREADS, lds, st>>>(dC, P, (const float *)Qp, (const float *)Kp, (const float *)V,
-                                                         (const float *)v, key_len, dQp, dKp, dV, dv_part, s.Tk, s.H,
-                                                         s.Dv, cw);
+    k_step_bwd<T, DEFER><<<grid, ST_THREADS, lds, st>>>(dC, P, (const T *)Qp, (const T *)Kp, (const T *)V,
+                                                        (const T *)v, key_len, dQp, dKp, dV, dv_part, ds_out,
+                                                        ds_sum_out, ds_rows, ds_row, ds_pitch(s.Tk), s.Tk, s.H, s.Dv,
+                                                        cw);
     return hipGetLastError();
+}
+
+hipError_t launch_step_bwd(const AttnShape &s, const float *dC, const float *P, const void *Qp, const void *Kp,
+                           const void *V, const void *v, const int *key_len, float *dQp, float *dKp, float *dV,
+                           float *dv_part, hipStream_t st) {
+    return s.bf16 ? launch_step_bwd_t<bf16_t, false>(s, dC, P, Qp, Kp, V, v, key_len, dQp, dKp, dV, dv_part, nullptr,
+                                                     nullptr, 1, 0, st)
+                  : launch_step_bwd_t<float, false>(s, dC, P, Qp, Kp, V, v, key_len, dQp, dKp, dV, dv_part, nullptr,
+                                                    nullptr, 1, 0, st);
+}
+
+hipError_t launch_step_bwd_query(const AttnShape &s, const float *dC, const float *P, const void *Qp, const void *Kp,
+                                 const void *V, const void *v, const int *key_len, float *dQp, float *ds_out,
+                                 float *ds_sum_out, int steps, int step, hipStream_t st) {
+    return s.bf16 ? launch_step_bwd_t<bf16_t, true>(s, dC, P, Qp, Kp, V, v, key_len, dQp, nullptr, nullptr, nullptr,
+                                                    ds_out, ds_sum_out, steps, step, st)
+                  : launch_step_bwd_t<float, true>(s, dC, P, Qp, Kp, V, v, key_len, dQp, nullptr, nullptr, nullptr,
+                                                   ds_out, ds_sum_out, steps, step, st);
 }
 
 }  // namespace echo

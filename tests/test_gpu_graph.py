@@ -10,8 +10,8 @@ from parity import assert_parity, oracle_outputs
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("one_launch", [False, True], ids=["general_kernels", "step_kernels"])
-def test_decoder_steps_from_a_graph(one_launch):
+@pytest.mark.parametrize("form", ["general_kernels", "step_kernels", "key_side_deferred"])
+def test_decoder_steps_from_a_graph(form):
     import torch
     assert torch.cuda.is_available(), "needs the GPU"
     from paper_1805_08899_amd import binding as eb, harness
@@ -54,7 +54,26 @@ def test_decoder_steps_from_a_graph(one_launch):
             eb.check(eb.echo_attn_bwd_accumulate(desc, dc[t], P[t], q[t], full.Kp, full.V, full.v, full.key_len,
                                                  dQ[t], dK, dV, dv, ws, stream=st))
 
-    sentence = sentence_step_kernels if one_launch else sentence_general
+    sent_desc = eb.make_desc(B, T, Tk, Hh, Dv, "f32")
+    ds_rows = torch.empty(eb.echo_attn_steps_ds_bytes(sent_desc), dtype=torch.uint8, device=dev)
+    ws_sent = torch.empty(eb.echo_attn_bwd_workspace_bytes(sent_desc), dtype=torch.uint8, device=dev)
+    P_all = torch.empty(B, T, Tk, **f32)
+
+    def sentence_deferred():
+        """Steps that only read; dKp, dV, dv by one call at the end (which runs inter-block flags through its
+        workspace: the replays below must find them in a usable state each time)."""
+        st = torch.cuda.current_stream(dev)
+        for t in range(T):
+            eb.check(eb.echo_attn_step_fwd(desc, q[t], full.Kp, full.V, full.v, full.key_len, ctx[t], P[t], stream=st))
+        for t in reversed(range(T)):
+            eb.check(eb.echo_attn_step_bwd_query(desc, t, T, dc[t], P[t], q[t], full.Kp, full.V, full.v, full.key_len,
+                                                 dQ[t], ds_rows, stream=st))
+        torch.cat(P, dim=1, out=P_all)
+        eb.check(eb.echo_attn_steps_bwd_keys(sent_desc, full.dC, P_all, full.Qp, full.Kp, full.v, full.key_len,
+                                             ds_rows, dK, dV, dv, ws_sent, stream=st))
+
+    sentence = {"general_kernels": sentence_general, "step_kernels": sentence_step_kernels,
+                "key_side_deferred": sentence_deferred}[form]
 
     def snapshot():
         torch.cuda.synchronize(dev)
@@ -63,8 +82,9 @@ def test_decoder_steps_from_a_graph(one_launch):
                 "dv": dv.cpu().numpy()}
 
     def poison():
-        for t in ctx + P + dQ + [dK, dV, dv, dvp]:
+        for t in ctx + P + dQ + [dK, dV, dv, dvp, P_all]:
             t.fill_(float("nan"))
+        ds_rows.fill_(0xFF)
 
     sentence()                                          # eager: also the warm-up before capture
     eager = snapshot()

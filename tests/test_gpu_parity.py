@@ -306,3 +306,20 @@ def test_decoder_steps_match_the_batched_layer(H, case):
             "dQp": torch.cat(dQ1, dim=1).cpu().numpy(), "dKp": dK1.cpu().numpy(), "dV": dV1.cpu().numpy(),
             "dv": dv1.cpu().numpy()}
     assert_parity(got1, ref, inputs, dt, name + " (one-launch steps)")
+    # the same steps with the key-side gradients deferred to one call per sentence
+    sent_desc = eb.make_desc(B, T, Tk, Hh, Dv, dt)
+    ds_rows = torch.full((eb.echo_attn_steps_ds_bytes(sent_desc),), 0xFF, dtype=torch.uint8, device=full.device)
+    ws2 = torch.full((eb.echo_attn_bwd_workspace_bytes(sent_desc),), 0xFF, dtype=torch.uint8, device=full.device)
+    dQ2 = [torch.full((B, 1, Hh), float("nan"), **f32) for _ in range(T)]
+    dK2, dV2 = torch.full((B, Tk, Hh), float("nan"), **f32), torch.full((B, Tk, Dv), float("nan"), **f32)
+    dv2 = torch.full((Hh,), float("nan"), **f32)
+    for t in reversed(range(T)):
+        eb.check(eb.echo_attn_step_bwd_query(step_desc, t, T, dc_steps[t], P1[t], q_steps[t], full.Kp, full.V, full.v,
+                                             full.key_len, dQ2[t], ds_rows, stream=st), "step bwd, query side")
+    P_all = torch.cat(P1, dim=1).contiguous()
+    eb.check(eb.echo_attn_steps_bwd_keys(sent_desc, full.dC, P_all, full.Qp, full.Kp, full.v, full.key_len, ds_rows,
+                                         dK2, dV2, dv2, ws2, stream=st), "sentence bwd, key side")
+    torch.cuda.synchronize(full.device)
+    got2 = dict(got1, dQp=torch.cat(dQ2, dim=1).cpu().numpy(), dKp=dK2.cpu().numpy(), dV=dV2.cpu().numpy(),
+                dv=dv2.cpu().numpy())
+    assert_parity(got2, ref, inputs, dt, name + " (key side deferred)")
