@@ -1,14 +1,16 @@
 #!/usr/bin/env python3
 """Benchmark of the additive-attention hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1] [--no-cpu-baseline] [--no-extras]
 
 One step = echo_attn_fwd followed by echo_attn_bwd over one resident batch of
 the chosen workload (default: workload 1, B=64, Tq=Tk=50, H=Dv=512, fp32).
 Prints ONE JSON line: whole-job fwd+bwd calls/s, the roofline of the dominant
 kernel (timed live with HIP events on the launch stream), the measured machine
-ceilings, peak device bytes beside the keep-the-feature-map variant, and the
-float64 oracle timed on the host cores as a reported baseline.
+ceilings, peak device bytes beside the keep-the-feature-map variant, the
+float64 oracle timed on the host cores as a reported baseline, and compact
+figures for the other rows of the build (per-step decoder form, one-bit
+dropout, LSTM cell block; --no-extras leaves them out).
 """
 from __future__ import annotations
 
@@ -28,16 +30,32 @@ if ROOT not in sys.path:
 PEAK_SLOTS = 256 * 4 * 32 * 2.4e9            # 78.6e12 slots/s
 PEAK_TFLOPS = 2 * PEAK_SLOTS / 1e12          # 157.3
 PEAK_HBM = 8.0e12
-# Issue slots per tanh evaluation of the two hot loops as written:
-#   forward score loop   fma, rcp, fma        -> 2 + 4 = 6 slots
-#   recompute loop       fma, rcp, 4 fma      -> 5 + 4 = 9 slots
-# and of the textbook form (add, exp, add, rcp, ... = 1 exp + 1 rcp + full-rate ops): 13 and 18 slots.
-SLOTS_ISSUED = {"fwd_fused": 6.0, "recompute": 9.0}
-SLOTS_CANONICAL = {"fwd_fused": 13.0, "recompute": 18.0}
+# Work per tanh evaluation ("unit") that `roofline.achieved` counts, in issue slots (one slot = one full-rate
+# lane operation = 2 flop; a reciprocal or exponential holds the pipe for 4):
+#   forward score    fma, rcp, fma        -> 2 + 4 = 6 slots      (the factorised evaluation, one element at a time)
+#   recompute        fma, rcp, 4 fma      -> 5 + 4 = 9 slots
+# The forward kernel now shares one reciprocal between two neighbouring h (2 fma, add, mul, rcp, fma per pair):
+# it ISSUES 4.5 slots per unit.  `frac` keeps the 6-slot figure so that it moves with the launch time alone and
+# stays comparable from build to build; `frac_issued` is the same with the slots actually issued.
+SLOTS_UNIT = {"fwd_fused": 6.0, "recompute": 9.0}
+SLOTS_ISSUED = {"fwd_fused": 4.5, "recompute": 9.0}
 CAL_MIX = {"fwd_fused": "fwd_mix_tanh_per_s", "recompute": "bwd_mix_tanh_per_s"}
-# HBM bytes per launch (fetch + write) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the
-# same counters read for the library's plain copy kernel; source: profiles/bench_cfg1_kernels_and_counters.txt
-TRAFFIC_FROM_PROFILE = {"cfg1_nmt_f32_B64_T50_H512": {"fwd_fused": 16.0e6 + 10.0e6, "recompute": 16.2e6 + 13.2e6}}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
+
+
+def traffic_from_profile(workload_name, kernel):
+    """HBM bytes per launch (fetch + write) of `kernel` at `workload_name`, from the tracked table that the
+    rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summaries under profiles/ are written from (lines: workload kernel
+    fetch_bytes write_bytes).  None if the table has no such line."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) == 4 and not line.startswith("#") and parts[0] == workload_name and parts[1] == kernel:
+                    return float(parts[2]) + float(parts[3])
+    except OSError:
+        pass
+    return None
 
 
 def main() -> int:
@@ -48,12 +66,11 @@ def main() -> int:
     ap.add_argument("--workload", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stash", action="store_true")
-    ap.add_argument("--dropout", action="store_true",
-                    help="also time the one-bit dropout codec (HBM-bound) on 64 Mi elements")
-    ap.add_argument("--lstm-cell", action="store_true",
-                    help="also time the LSTM cell's non-linear block, recompute against stash (HBM-bound)")
-    ap.add_argument("--decoder-steps", action="store_true",
-                    help="also time the per-step decoder form of the same workload (Tq calls with one query each)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="leave out the per-step decoder form, the one-bit dropout codec and the LSTM cell block")
+    ap.add_argument("--dropout", action="store_true", help="(kept for old command lines; the codec is timed by default)")
+    ap.add_argument("--lstm-cell", action="store_true", help="(kept for old command lines; timed by default)")
+    ap.add_argument("--decoder-steps", action="store_true", help="(kept for old command lines; timed by default)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (a batch would shard over its samples with "
@@ -139,6 +156,7 @@ def main() -> int:
     # kernels share what their bracketed sum exceeds the backward-only loop by, in equal parts.
     fwd_names = [k for k in kernels if k in ("fwd_fused", "score", "softmax", "context")]
     bwd_names = [k for k in kernels if k not in fwd_names]
+    # the recompute launch also finishes dv (the blocks that start last wait for all parts): that tail is in its time
     for names, loop_ms in ((fwd_names, fwd_ms), (bwd_names, bwd_ms)):
         if names:
             excess = (sum(kernels[k]["avg_us"] for k in names) - 1e3 * loop_ms) / len(names)
@@ -148,34 +166,34 @@ def main() -> int:
 
     def alu_roofline(name):
         us = kernels[name].get("avg_us_in_loop", kernels[name]["avg_us"])
-        slots = SLOTS_ISSUED[name] * n4u
-        achieved = 2 * slots / (us * 1e-6) / 1e12
+        achieved = 2 * SLOTS_UNIT[name] * n4u / (us * 1e-6) / 1e12
         mix = cal.get(CAL_MIX[name])
         return {
             "kernel": name, "bound": "alu", "achieved": achieved, "peak": PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": achieved / PEAK_TFLOPS,
-            "traffic": TRAFFIC_FROM_PROFILE.get(wl.name, {}).get(name),
+            "traffic": traffic_from_profile(wl.name, name),
             "avg_launch_us": us, "avg_launch_us_single_bracketed": kernels[name]["avg_us"],
             "tanh_evals_per_launch": n4u,
+            "slots_per_tanh": SLOTS_UNIT[name],
             "slots_per_tanh_issued": SLOTS_ISSUED[name],
-            "frac_canonical_form": 2 * SLOTS_CANONICAL[name] * n4u / (us * 1e-6) / 1e12 / PEAK_TFLOPS,
-            "frac_of_measured_mix_ceiling": (n4u / (us * 1e-6)) / mix if mix else None,
+            "frac_issued": 2 * SLOTS_ISSUED[name] * n4u / (us * 1e-6) / 1e12 / PEAK_TFLOPS,
+            "information_only": {"frac_of_measured_mix_ceiling": (n4u / (us * 1e-6)) / mix if mix else None},
         }
 
     dom_us = kernels[dominant]["avg_us"]
-    if dominant in SLOTS_ISSUED:
+    if dominant in SLOTS_UNIT:
         roofline = alu_roofline(dominant)
     else:
         roofline = {"kernel": dominant, "bound": "hbm", "achieved": None, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
                     "frac": None, "traffic": None, "avg_launch_us": dom_us}
-    hot_rooflines = {k: alu_roofline(k) for k in SLOTS_ISSUED if k in kernels}
+    hot_rooflines = {k: alu_roofline(k) for k in SLOTS_UNIT if k in kernels}
 
     # end-to-end roofline time: arithmetic slots of both hot loops against the HBM minimum
     s_in = 2 if wl.in_dtype == "bf16" else 4
     io_bytes = ((wl.B * wl.Tq * wl.H + wl.B * wl.Tk * wl.H + wl.B * wl.Tk * wl.Dv) * s_in * 2   # fwd + bwd reads
                 + 4 * (wl.B * wl.Tq * wl.Dv * 2 + wl.B * wl.Tq * wl.Tk * 2)                      # C, dC, P w+r
                 + 4 * (wl.B * wl.Tq * wl.H + wl.B * wl.Tk * wl.H + wl.B * wl.Tk * wl.Dv))         # dQp, dKp, dV
-    t_alu = (SLOTS_ISSUED["fwd_fused"] + SLOTS_ISSUED["recompute"]) * n4u / PEAK_SLOTS
+    t_alu = (SLOTS_UNIT["fwd_fused"] + SLOTS_UNIT["recompute"]) * n4u / PEAK_SLOTS
     t_hbm = io_bytes / PEAK_HBM
     end_to_end = {"t_alu_us": t_alu * 1e6, "t_hbm_us": t_hbm * 1e6, "io_bytes": io_bytes,
                   "frac": max(t_alu, t_hbm) / (ms_per_step_events * 1e-3)}
@@ -203,10 +221,14 @@ def main() -> int:
         del dbs
         torch.cuda.empty_cache()
 
-    decoder = decoder_steps(eb, harness, torch, wl, inputs, dev) if args.decoder_steps else None
-    dropout = dropout_codec(eb, torch, dev, cpu=not args.no_cpu_baseline) if args.dropout else None
-    lstm = lstm_cell(eb, torch, dev, cpu=not args.no_cpu_baseline) if args.lstm_cell else None
     cpu = None if args.no_cpu_baseline else cpu_baseline(wl, inputs)
+    extras = not args.no_extras
+    # the per-step form is timed at workload 1's shapes whatever --workload says (it is the translation model's)
+    wl_dec = WORKLOADS[1]
+    decoder = decoder_steps(eb, harness, torch, wl_dec, inputs if wl is wl_dec else make_inputs(wl_dec), dev,
+                            cpu=cpu if wl is wl_dec else None) if extras else None
+    dropout = dropout_codec(eb, torch, dev, cpu=not args.no_cpu_baseline) if extras else None
+    lstm = lstm_cell(eb, torch, dev, cpu=not args.no_cpu_baseline) if extras else None
 
     out = {
         "metric": "attention fwd+bwd calls/s",
@@ -271,7 +293,7 @@ def calibrate(eb, torch, dev):
     return out
 
 
-def decoder_steps(eb, harness, torch, wl, inputs, dev, reps=20):
+def decoder_steps(eb, harness, torch, wl, inputs, dev, reps=20, cpu=None):
     """The same batch as Tq decoder steps of one query each (the shape the translation model's decoder produces):
     Tq forward calls, then Tq accumulating backward calls; launched one by one and replayed from a HIP graph."""
     full = harness.DeviceBatch(wl, inputs, device=dev)
@@ -343,13 +365,49 @@ def decoder_steps(eb, harness, torch, wl, inputs, dev, reps=20):
     torch.cuda.current_stream(dev).wait_stream(side)
     graph1.replay()
     fgraph_wall, fgraph_gpu = timed(graph1.replay)
-    return {"steps": T, "launches_per_sentence": 4 * T + 3,
-            "one_launch_steps": {"launches_per_sentence": 2 * T + 4, "ms_per_sentence": fused_wall,
-                                 "gpu_ms_per_sentence": fused_gpu, "graph_gpu_ms_per_sentence": fgraph_gpu,
-                                 "graph_us_per_step_fwd_bwd": 1e3 * fgraph_gpu / T},
-            "eager_ms_per_sentence": eager_wall, "eager_gpu_ms_per_sentence": eager_gpu,
-            "graph_ms_per_sentence": graph_wall, "graph_gpu_ms_per_sentence": graph_gpu,
-            "graph_us_per_step_fwd_bwd": 1e3 * graph_gpu / T}
+    # key-side gradients deferred: steps that only read, then one call per sentence for dKp, dV, dv
+    sent_desc = eb.make_desc(wl.B, T, wl.Tk, wl.H, wl.Dv, wl.in_dtype)
+    ds_rows = torch.empty(eb.echo_attn_steps_ds_bytes(sent_desc), dtype=torch.uint8, device=dev)
+    ws_sent = torch.empty(eb.echo_attn_bwd_workspace_bytes(sent_desc), dtype=torch.uint8, device=dev)
+    P_all = torch.empty(wl.B, T, wl.Tk, **f32)
+
+    def sentence_deferred():
+        st = torch.cuda.current_stream(dev)
+        for t in range(T):       # with a workspace the forward call may spread a sample over several blocks
+            eb.check(eb.echo_attn_fwd(desc, q[t], full.Kp, full.V, full.v, full.key_len, ctx[t], P[t], ws, stream=st))
+        for t in reversed(range(T)):
+            eb.check(eb.echo_attn_step_bwd_query(desc, t, T, dc[t], P[t], q[t], full.Kp, full.V, full.v, full.key_len,
+                                                 dQ[t], ds_rows, stream=st))
+        torch.cat(P, dim=1, out=P_all)
+        eb.check(eb.echo_attn_steps_bwd_keys(sent_desc, full.dC, P_all, full.Qp, full.Kp, full.v, full.key_len,
+                                             ds_rows, dK, dV, dv, ws_sent, stream=st))
+
+    for _ in range(3):
+        sentence_deferred()
+    def_wall, def_gpu = timed(sentence_deferred)
+    side.wait_stream(torch.cuda.current_stream(dev))
+    graph2 = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph2, stream=side):
+            sentence_deferred()
+    torch.cuda.current_stream(dev).wait_stream(side)
+    graph2.replay()
+    dgraph_wall, dgraph_gpu = timed(graph2.replay)
+    out = {"workload": wl.name, "steps": T,
+           "general_kernels": {"launches_per_sentence": 3 * T + 3, "eager_gpu_ms_per_sentence": eager_gpu,
+                               "graph_gpu_ms_per_sentence": graph_gpu, "graph_us_per_step_fwd_bwd": 1e3 * graph_gpu / T},
+           "one_launch_steps": {"launches_per_sentence": 2 * T + 4, "eager_gpu_ms_per_sentence": fused_gpu,
+                                "graph_gpu_ms_per_sentence": fgraph_gpu,
+                                "graph_us_per_step_fwd_bwd": 1e3 * fgraph_gpu / T},
+           "key_side_deferred": {"launches_per_sentence": 2 * T + 3, "eager_gpu_ms_per_sentence": def_gpu,
+                                 "graph_gpu_ms_per_sentence": dgraph_gpu,
+                                 "graph_us_per_step_fwd_bwd": 1e3 * dgraph_gpu / T},
+           "us_per_step_fwd_bwd": 1e3 * min(dgraph_gpu, def_gpu, fgraph_gpu, fused_gpu) / T}
+    if cpu is not None:
+        # the oracle has no per-step form: its call on the steps stacked along Tq is the same float64 work
+        out["cpu_baseline"] = {"value": cpu["value"] * T, "unit": "steps/s (fwd+bwd)", "cores": cpu["cores"],
+                               "kind": "oracle", "sample": "the oracle call on the stacked steps: " + cpu["sample"]}
+    return out
 
 
 def dropout_codec(eb, torch, dev, n=1 << 26, p=0.1, reps=20, cpu=True):

@@ -98,14 +98,22 @@ typedef struct {
  * state that persists from forward to backward is P (Section 5.1).
  * The forward pass needs none (0 is returned, and echo_attn_fwd then accepts workspace == NULL) whenever its
  * one-kernel form runs, which keeps the scores on chip: H a multiple of 4 and a tile of eight query rows
- * within on-chip memory, i.e. every shape of practical size; otherwise B*Tq*Tk floats for the scores. */
+ * within on-chip memory, i.e. every shape of practical size; otherwise B*Tq*Tk floats for the scores.
+ * Exception, decoder steps: for Tq == 1, Tk <= 64, H and Dv multiples of 4 up to 512 and B <= 64 the forward call
+ * asks for 4 KB per sample, through which the four blocks that share a sample pass the scores to one another (see
+ * echo_attn_fwd). */
 size_t echo_attn_fwd_workspace_bytes(const echo_attn_desc_t *desc);
 size_t echo_attn_bwd_workspace_bytes(const echo_attn_desc_t *desc);
 
 /* Forward (Section 2, steps 1-2; scoring function of Section 4.1).
  *   in : Qp [B,Tq,H], Kp [B,Tk,H], V [B,Tk,Dv], v [H]   (in_dtype), key_len [B] int32
  *   out: context [B,Tq,Dv] fp32, P [B,Tq,Tk] fp32 (keep it for the backward call)
- * The tanh map is never written to memory. */
+ * The tanh map is never written to memory.
+ * Tq == 1 is a decoder step (Section 2: one query per sample against the same encoder states) and runs the
+ * kernels made for it.  On a short key axis (the shapes listed at echo_attn_fwd_workspace_bytes) a sample is
+ * spread over four blocks that wait for one another's scores, bounded by 2 s: if the GPU is so occupied by other
+ * work that the four do not get to run together within that time, context and P of the call are NaN.  The
+ * workspace then carries the scores between them: one call at a time per workspace, also across streams. */
 echo_status_t echo_attn_fwd(const echo_attn_desc_t *desc,
                             const void *Qp, const void *Kp, const void *V, const void *v,
                             const int32_t *key_len,
@@ -185,7 +193,10 @@ echo_status_t echo_attn_step_finish(const echo_attn_desc_t *desc, const float *d
  *       re-evaluates tanh (Section 3.4) and writes dQp [B,1,H]; it also leaves the step's row of dS and its sum in
  *       `ds_rows`, a device buffer of echo_attn_steps_ds_bytes(sentence descriptor) bytes that the caller keeps
  *       for the sentence (any initial state).  It reads Kp and V once and writes nothing else.  `desc` has
- *       Tq == 1; `step` in [0, steps) is the position of this step in the stacked tensors below.
+ *       Tq == 1; `step` in [0, steps) is the position of this step in the stacked tensors below.  On a short key
+ *       axis it spreads a sample over four blocks as echo_attn_fwd does with Tq == 1 (same shapes, same bounded
+ *       wait, dQp and the step's row NaN if it runs out); `ds_rows` carries what they exchange, so the step calls
+ *       of one `ds_rows` must not overlap one another.
  *   echo_attn_steps_bwd_keys   (once per sentence, after all steps) forms dKp [B,Tk,H], dV [B,Tk,Dv] and dv [H]
  *       (overwritten) from the steps stacked along Tq: dContext [B,steps,Dv], P [B,steps,Tk], Qp [B,steps,H], and
  *       `ds_rows` as the steps left it.  `desc` has Tq == steps.  Workspace: echo_attn_bwd_workspace_bytes(desc).

@@ -57,6 +57,7 @@ BwdWs bwd_layout(const AttnShape &s) {
 }
 // scores S [B,Tq,Tk] of the unfused forward kernels; the fused kernel keeps them in LDS and needs nothing
 size_t fwd_bytes(const AttnShape &s, bool want_map) {
+    if (!want_map && s.Tq == 1 && echo::step_split_mail_bytes(s) > 0) return align_up(echo::step_split_mail_bytes(s));
     if (!want_map && echo::fwd_fused_supported(s)) return 0;
     return align_up((size_t)s.B * s.Tq * s.Tk * sizeof(float));
 }
@@ -123,6 +124,17 @@ echo_status_t fwd_impl(const echo_attn_desc_t *desc, const void *Qp, const void 
     if (workspace_bytes < need) return ECHO_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     float *S = static_cast<float *>(workspace);
+    if (!want_map && s.Tq == 1) {             // a decoder step: the kernels made for one query per sample
+        if (echo::step_split_applicable(s)) {
+            ECHO_LAUNCH("step_fwd_split", echo::launch_step_fwd_split(s, Qp, Kp, V, v, key_len, context, P, workspace,
+                                                                      next_launch_number(), st));
+            return ECHO_OK;
+        }
+        if (echo::step_lds_bytes(s) <= 64 * 1024) {
+            ECHO_LAUNCH("step_fwd", echo::launch_step_fwd(s, Qp, Kp, V, v, key_len, context, P, st));
+            return ECHO_OK;
+        }
+    }
     if (!want_map && echo::fwd_fused_supported(s)) {
         ECHO_LAUNCH("fwd_fused", echo::launch_fwd_fused(s, Qp, Kp, V, v, key_len, context, P, st));
         return ECHO_OK;
@@ -192,6 +204,16 @@ echo_status_t static_scratch(void **out) {
     }
     *out = g_scratch_ptr[dev];
     return ECHO_OK;
+}
+
+// The per-sentence buffer of the deferred decoder form: [B, steps, ds_pitch(Tk)] rows of dS, [B, steps] row sums,
+// then the mail area of the steps' four-block form (empty where that form does not apply).
+AttnShape one_step(AttnShape s) {
+    s.Tq = 1;
+    return s;
+}
+size_t steps_mail_offset(const AttnShape &s, int steps) {
+    return align_up((size_t)s.B * steps * echo::ds_pitch(s.Tk) * sizeof(float)) + align_up((size_t)s.B * steps * sizeof(float));
 }
 
 }  // namespace
@@ -295,7 +317,7 @@ echo_status_t echo_attn_step_bwd(const echo_attn_desc_t *desc, const float *dCon
 size_t echo_attn_steps_ds_bytes(const echo_attn_desc_t *desc) {
     AttnShape s;
     if (check_desc(desc, &s) != ECHO_OK) return 0;
-    return align_up((size_t)s.B * s.Tq * echo::ds_pitch(s.Tk) * sizeof(float)) + align_up((size_t)s.B * s.Tq * sizeof(float));
+    return steps_mail_offset(s, s.Tq) + align_up(echo::step_split_mail_bytes(one_step(s)));
 }
 
 echo_status_t echo_attn_step_bwd_query(const echo_attn_desc_t *desc, int32_t step, int32_t steps,
@@ -315,6 +337,13 @@ echo_status_t echo_attn_step_bwd_query(const echo_attn_desc_t *desc, int32_t ste
     float *ds_sum = reinterpret_cast<float *>(static_cast<char *>(ds_rows) +
                                               align_up((size_t)s.B * steps * echo::ds_pitch(s.Tk) * sizeof(float)));
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (echo::step_split_applicable(s)) {
+        void *mail = static_cast<char *>(ds_rows) + steps_mail_offset(s, steps);
+        ECHO_LAUNCH("step_bwd_query_split",
+                    echo::launch_step_bwd_query_split(s, dContext, P, Qp, Kp, V, v, key_len, dQp, ds, ds_sum, steps,
+                                                      step, mail, next_launch_number(), st));
+        return ECHO_OK;
+    }
     ECHO_LAUNCH("step_bwd_query",
                 echo::launch_step_bwd_query(s, dContext, P, Qp, Kp, V, v, key_len, dQp, ds, ds_sum, steps, step, st));
     return ECHO_OK;

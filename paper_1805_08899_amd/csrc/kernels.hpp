@@ -80,4 +80,20 @@ hipError_t launch_step_bwd_query(const AttnShape &s, const float *dC, const floa
                                  const void *V, const void *v, const int *key_len, float *dQp, float *ds_out,
                                  float *ds_sum_out, int steps, int step, hipStream_t st);
 
+// Decoder steps on a short key axis (Tk <= 64, H and Dv multiples of 4 up to 512, B <= kStepSplitMaxB) with a
+// sample spread over four blocks that exchange one float per key through `mail` (step_split_mail_bytes(s) bytes of
+// device memory in any state, used by one launch at a time; 0 bytes: the shape does not qualify).
+// step_split_applicable: the shape qualifies and the current device runs all 4 B blocks at once.
+// epoch: a number no earlier launch on this mail area used (never 0).
+constexpr int kStepSplitMaxB = 64;
+size_t step_split_mail_bytes(const AttnShape &s);
+bool step_split_applicable(const AttnShape &s);
+hipError_t launch_step_fwd_split(const AttnShape &s, const void *Qp, const void *Kp, const void *V, const void *v,
+                                 const int *key_len, float *C, float *P, void *mail, unsigned long long epoch,
+                                 hipStream_t st);
+hipError_t launch_step_bwd_query_split(const AttnShape &s, const float *dC, const float *P, const void *Qp,
+                                       const void *Kp, const void *V, const void *v, const int *key_len, float *dQp,
+                                       float *ds_out, float *ds_sum_out, int steps, int step, void *mail,
+                                       unsigned long long epoch, hipStream_t st);
+
 }  // namespace echo

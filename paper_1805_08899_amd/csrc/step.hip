@@ -199,37 +199,38 @@ __global__ __launch_bounds__(ST_THREADS) void k_step_fwd(
     // ---- scores: S[j] = sum_h v[h] tanh(q[h] + k[j,h]),  tanh = 1 - 2 / (exp(2 (q + k)) + 1)
     for (int n = 0; n < n_batch; ++n) {
         const int j0 = 8 * ST_KB * n + ST_KB * w;
-        if (j0 >= L) break;                                       // wave-uniform
         float acc[ST_KB] = {0.f, 0.f, 0.f, 0.f};
-        for (int h = 4 * lane; h < H4; h += 256) {
-            const float4 q4 = ld4(qb, (size_t)h), v4 = ld4(v, (size_t)h);
-            float4 k4[ST_KB];
+        if (j0 < L) {                                             // wave-uniform
+            for (int h = 4 * lane; h < H4; h += 256) {
+                const float4 q4 = ld4(qb, (size_t)h), v4 = ld4(v, (size_t)h);
+                float4 k4[ST_KB];
 #pragma unroll
-            for (int u = 0; u < ST_KB; ++u) k4[u] = ld4(Kb, (size_t)min(j0 + u, L - 1) * H + h);
+                for (int u = 0; u < ST_KB; ++u) k4[u] = ld4(Kb, (size_t)min(j0 + u, L - 1) * H + h);
 #pragma unroll
-            for (int u = 0; u < ST_KB; ++u) {
+                for (int u = 0; u < ST_KB; ++u) {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const float x = kTwoLog2e * (comp4(q4, c) + comp4(k4[u], c));
-                    acc[u] += comp4(v4, c) * __builtin_fmaf(-2.f, fast_rcp(fast_exp2(x) + 1.0f), 1.0f);
+                    for (int c = 0; c < 4; ++c) {
+                        const float x = kTwoLog2e * (comp4(q4, c) + comp4(k4[u], c));
+                        acc[u] += comp4(v4, c) * __builtin_fmaf(-2.f, fast_rcp(fast_exp2(x) + 1.0f), 1.0f);
+                    }
                 }
             }
-        }
-        for (int h = H4 + lane; h < H; h += 64) {                 // rows that do not start aligned: one element at a time
-            const float qh = ld(qb, (size_t)h), vh = ld(v, (size_t)h);
+            for (int h = H4 + lane; h < H; h += 64) {             // rows that do not start aligned: one element at a time
+                const float qh = ld(qb, (size_t)h), vh = ld(v, (size_t)h);
+#pragma unroll
+                for (int u = 0; u < ST_KB; ++u) {
+                    const float x = kTwoLog2e * (qh + ld(Kb, (size_t)min(j0 + u, L - 1) * H + h));
+                    acc[u] += vh * __builtin_fmaf(-2.f, fast_rcp(fast_exp2(x) + 1.0f), 1.0f);
+                }
+            }
 #pragma unroll
             for (int u = 0; u < ST_KB; ++u) {
-                const float x = kTwoLog2e * (qh + ld(Kb, (size_t)min(j0 + u, L - 1) * H + h));
-                acc[u] += vh * __builtin_fmaf(-2.f, fast_rcp(fast_exp2(x) + 1.0f), 1.0f);
+                const float tot = wave_sum(acc[u]);
+                if (lane == 0 && j0 + u < L) s_s[j0 + u] = tot;
             }
         }
-#pragma unroll
-        for (int u = 0; u < ST_KB; ++u) {
-            const float tot = wave_sum(acc[u]);
-            if (lane == 0 && j0 + u < L) s_s[j0 + u] = tot;
-        }
     }
-    __syncthreads();
+    lds_barrier();
 
     // ---- softmax over the valid keys: every wave forms the maximum and the sum itself (same arithmetic in all)
     float mx = -INFINITY;
@@ -239,13 +240,13 @@ __global__ __launch_bounds__(ST_THREADS) void k_step_fwd(
     for (int j = lane; j < L; j += 64) z += fast_exp2((s_s[j] - mx) * 1.4426950408889634f);
     z = wave_sum(z);
     const float inv = 1.0f / z;
-    __syncthreads();
+    lds_barrier();
     for (int j = threadIdx.x; j < Tk; j += ST_THREADS) {
         const float p = j < L ? fast_exp2((s_s[j] - mx) * 1.4426950408889634f) * inv : 0.f;
         if (j < L) s_s[j] = p;
         store_streaming(&Pb[j], p);
     }
-    __syncthreads();
+    lds_barrier();
 
     // ---- context: a thread per column, eight value rows in flight
     for (int d = threadIdx.x; d < Dv; d += ST_THREADS) {
@@ -262,8 +263,108 @@ __global__ __launch_bounds__(ST_THREADS) void k_step_fwd(
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// Short key axes (Tk <= 64, the sentence lengths of Section 2's translation model) with H and Dv up to 512.
+// A step on a few dozen keys is a chain of trips to memory, not arithmetic: measured at 64 samples of 50 keys, the
+// general kernels spend their time in four dependent rounds of key loads (two batches of keys, two chunks of h)
+// after a first trip for key_len, and in waiting for the acknowledgement of the P stores before the value rows are
+// used.  Here every load of the step is requested before the first result is awaited -- key rows are clamped with
+// Tk, not with the length, so nothing waits for key_len; rows at or beyond the length are loaded and never used
+// -- and all stores come last.  Wave w takes keys w, w + 8, ...; with at most 64 keys every wave holds the whole
+// score row (one key per lane), so the softmax needs no LDS pass and the context takes its weights by lane reads.
+constexpr int SS_KEYS = 64;               // keys a short step covers at most
+constexpr int SS_KU = SS_KEYS / ST_W;     // keys per wave
+constexpr int SS_CH = 2;                  // chunks of 256 along h
+constexpr int SS_MAX_WIDTH = 256 * SS_CH;
+
+template <typename T>
+__global__ __launch_bounds__(ST_THREADS) void k_step_fwd_short(
+    const T *__restrict__ Qp, const T *__restrict__ Kp, const T *__restrict__ V, const T *__restrict__ v,
+    const int *__restrict__ key_len, float *__restrict__ C, float *__restrict__ P, int Tk, int H, int Dv) {
+    __shared__ float s_s[SS_KEYS];
+    const int b = blockIdx.x;
+    const int lane = lane_id();
+    const int w = __builtin_amdgcn_readfirstlane(wave_id());
+    const T *qb = Qp + (size_t)b * H;
+    const T *Kb = Kp + (size_t)b * Tk * H;
+    const T *Vb = V + (size_t)b * Tk * Dv;
+
+    // ---- every request of the step
+    const int len_raw = key_len[b];
+    float4 q4[SS_CH], v4[SS_CH], k4[SS_CH][SS_KU];
+#pragma unroll
+    for (int c = 0; c < SS_CH; ++c) {
+        if (256 * c < H) {                                        // block-uniform
+            const int h = 256 * c + 4 * lane;
+            const int hc = min(h, H - 4);
+            q4[c] = ld4(qb, (size_t)hc);
+            v4[c] = ld4(v, (size_t)hc);
+            if (h >= H) v4[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int u = 0; u < SS_KU; ++u) k4[c][u] = ld4(Kb, (size_t)min(w + ST_W * u, Tk - 1) * H + hc);
+        }
+    }
+    float vrow[SS_KEYS];                                          // this thread's column of the value rows
+    const int d_own = min((int)threadIdx.x, Dv - 1);
+#pragma unroll
+    for (int j = 0; j < SS_KEYS; ++j)
+        if (j < Tk) vrow[j] = ld(Vb, (size_t)j * Dv + d_own);
+    const int L = clamp_len(len_raw, Tk);
+
+    // ---- scores: S[j] = sum_h v[h] tanh(q[h] + k[j,h]),  tanh = 1 - 2 / (exp(2 (q + k)) + 1)
+#pragma unroll
+    for (int u = 0; u < SS_KU; ++u) {
+        const int j = w + ST_W * u;
+        if (j < L) {                                              // wave-uniform
+            float acc = 0.f;
+#pragma unroll
+            for (int c = 0; c < SS_CH; ++c) {
+                if (256 * c < H) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float x = kTwoLog2e * (comp4(q4[c], e) + comp4(k4[c][u], e));
+                        acc += comp4(v4[c], e) * __builtin_fmaf(-2.f, fast_rcp(fast_exp2(x) + 1.0f), 1.0f);
+                    }
+                }
+            }
+            const float tot = wave_sum(acc);
+            if (lane == 0) s_s[j] = tot;
+        }
+    }
+    lds_barrier();
+
+    // ---- softmax over the valid keys, one key per lane, the same in every wave
+    const float sc = lane < L ? s_s[lane] : -INFINITY;
+    const float mx = wave_max(sc);
+    const float ex = lane < L ? fast_exp2((sc - mx) * 1.4426950408889634f) : 0.f;
+    const float z = wave_sum(ex);
+    const float p = lane < L ? ex * (1.0f / z) : 0.f;
+
+    // ---- context: a thread per column, the value rows are in registers
+    float acc = 0.f;
+#pragma unroll
+    for (int j = 0; j < SS_KEYS; ++j)
+        if (j < L) acc = __builtin_fmaf(lane_value(p, j), vrow[j], acc);
+    if ((int)threadIdx.x < Dv) store_streaming(&C[(size_t)b * Dv + threadIdx.x], acc);
+    if (w == 0 && lane < Tk) store_streaming(&P[(size_t)b * Tk + lane], p);
+}
+
+static bool step_fwd_short_ok(const AttnShape &s) {
+    return s.Tk <= SS_KEYS && s.H % 4 == 0 && s.H >= 4 && s.H <= SS_MAX_WIDTH && s.Dv <= ST_THREADS;
+}
+
 hipError_t launch_step_fwd(const AttnShape &s, const void *Qp, const void *Kp, const void *V, const void *v,
                            const int *key_len, float *C, float *P, hipStream_t st) {
+    if (step_fwd_short_ok(s)) {
+        if (s.bf16)
+            k_step_fwd_short<bf16_t><<<s.B, ST_THREADS, 0, st>>>((const bf16_t *)Qp, (const bf16_t *)Kp,
+                                                                 (const bf16_t *)V, (const bf16_t *)v, key_len, C, P,
+                                                                 s.Tk, s.H, s.Dv);
+        else
+            k_step_fwd_short<float><<<s.B, ST_THREADS, 0, st>>>((const float *)Qp, (const float *)Kp, (const float *)V,
+                                                                (const float *)v, key_len, C, P, s.Tk, s.H, s.Dv);
+        return hipGetLastError();
+    }
     const size_t lds = (size_t)s.Tk * sizeof(float);
     if (lds > 64 * 1024) return hipErrorInvalidValue;
     if (lds > 48 * 1024) {

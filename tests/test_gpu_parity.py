@@ -245,6 +245,9 @@ STEP_CASES = [
     ("steps_bf16", 6, 4, 21, 128, 64, "bf16"),
     ("steps_ragged_h_many_keys", 3, 3, 77, 70, 36, "f32"),
     ("steps_h_not_multiple_of_4", 2, 2, 11, 33, 8, "f32"),
+    ("steps_64_keys_ragged_second_chunk", 5, 3, 64, 260, 264, "f32"),      # the short-axis kernels at their limit
+    ("steps_65_keys", 3, 2, 65, 64, 32, "bf16"),                           # one key beyond it
+    ("steps_with_empty_samples", 9, 2, 6, 32, 16, "f32"),                  # key_len drawn from 0..Tk
 ]
 
 
@@ -257,8 +260,10 @@ def test_decoder_steps_match_the_batched_layer(H, case):
     from paper_1805_08899_amd import binding as eb
     name, B, T, Tk, Hh, Dv, dt = case
     print("decoder steps", case, flush=True)
-    wl = Workload(name, B, T, Tk, Hh, Dv, dt, 0.5, 1, Tk, dt == "bf16")
+    wl = Workload(name, B, T, Tk, Hh, Dv, dt, 0.5, 0 if "empty" in name else 1, Tk, dt == "bf16")
     inputs = make_inputs(wl, seed=4321 + T)
+    if "empty" in name:
+        inputs["key_len"][0] = 0                          # at least one sample without a valid key
     ref = oracle_outputs(inputs, workers=1)
     full = H.DeviceBatch(wl, inputs)                     # device copies of Kp, V, v, key_len, dC
     step_desc = eb.make_desc(B, 1, Tk, Hh, Dv, dt)
