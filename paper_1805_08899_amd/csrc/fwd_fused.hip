@@ -28,8 +28,8 @@
 // pass boundaries, and the first value rows leave before the softmax.
 //
 // Placement.  The hardware hands blocks to the XCDs round-robin.  For small
-// batches every wave ranks the samples by valid keys itself (lengths in
-// registers, no LDS, no barrier), deals them to the XCDs in snake order (equal
+// batches one wave of the block ranks the samples by valid keys (lengths in
+// registers) and hands the block's sample to the other waves through LDS; samples go to the XCDs in snake order (equal
 // work per XCD, all tiles of a sample share one L2) and, when two blocks share
 // a CU, gives the CUs that hold one block the heaviest tiles and pairs heavy
 // with light tiles on the others; with more rounds of blocks the heaviest

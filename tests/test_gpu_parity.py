@@ -188,6 +188,43 @@ def test_large_preactivations_take_the_exact_path(H):
     assert_parity(got, ref, inputs, "f32", "saturating")
 
 
+def test_extreme_entries_of_v(H):
+    """The forward kernel divides by v (v r = 1 / (1/v + (exp(2q)/v) exp(2k))) and lets two neighbouring h share a
+    reciprocal: entries of v that are zero, denormal or tiny must count as zero without disturbing their
+    neighbour in the pair, whichever of the two they are, and a pair of them must vanish."""
+    wl = Workload("tiny_v", 3, 9, 13, 64, 8, "f32", 0.5, 1, 13)
+    inputs = make_inputs(wl, seed=91)
+    v = inputs["v"]
+    v[0] = 0.0            # first of a pair, neighbour ordinary
+    v[3] = 1e-20          # second of a pair
+    v[4] = -1e-30
+    v[5] = 1e-38          # a pair of negligible entries, one of them denormal
+    v[10] = -0.0
+    v[11] = 0.0           # a pair of zeros
+    v[17] = 1e-17         # just above the cut: kept
+    print("tiny v case", flush=True)
+    _, got = run_gpu(H, wl, inputs)
+    ref = oracle_outputs(inputs, workers=1)
+    assert_parity(got, ref, inputs, "f32", "tiny v")
+
+
+def test_huge_entries_of_v_take_the_exact_path(H):
+    """|v| beyond 1e15 would let products of two 1/v underflow: such blocks take the routine that exponentiates the
+    sum.  The scores are then of the order of 1e16 and the softmax picks one key; forward outputs against the
+    oracle, gradients finite (they are differences of rounding errors on both sides)."""
+    wl = Workload("huge_v", 2, 9, 13, 64, 8, "f32", 0.5, 2, 13)
+    inputs = make_inputs(wl, seed=92)
+    inputs["v"][7] = 3e15
+    inputs["v"][20] = -2e16
+    print("huge v case", flush=True)
+    _, got = run_gpu(H, wl, inputs)
+    ref = oracle_outputs(inputs, workers=1)
+    for k in ("context", "P"):
+        assert rel_err(got[k], ref[k]) <= 1e-4, k
+    for k in ("dQp", "dKp", "dV", "dv"):
+        assert np.isfinite(got[k]).all(), k
+
+
 @pytest.mark.parametrize("idx", [0, 1])
 def test_stash_variant_matches(H, idx):
     """The keep-the-feature-map baseline gives the same results, and its map
