@@ -225,21 +225,31 @@ def test_huge_entries_of_v_take_the_exact_path(H):
         assert np.isfinite(got[k]).all(), k
 
 
-@pytest.mark.parametrize("idx", [0, 1])
+@pytest.mark.parametrize("idx", [0, 1, 2, 3, 4])
 def test_stash_variant_matches(H, idx):
-    """The keep-the-feature-map baseline gives the same results, and its map
-    holds tanh(Qp + Kp) at the valid keys."""
+    """The keep-the-feature-map baseline gives the same results, and its map holds tanh(Qp + Kp) at the valid
+    keys.  Workloads 0 and 1 against the oracle; the large ones (maps of 1.3 to 11.8 GB) against the recomputing
+    path on the same inputs, which test_workload_parity holds to the oracle, and on sampled entries of the map."""
     wl = WORKLOADS[idx]
     print("stash variant", wl.name, flush=True)
     inputs = make_inputs(wl)
     db, got = run_gpu(H, wl, inputs, stash=True)
-    ref = oracle_outputs(inputs, workers=1 if idx == 0 else None)
-    assert_parity(got, ref, inputs, wl.in_dtype, wl.name + " (stash)")
+    if idx <= 1:
+        ref = oracle_outputs(inputs, workers=1 if idx == 0 else None)
+        assert_parity(got, ref, inputs, wl.in_dtype, wl.name + " (stash)")
+    else:
+        _, rec = run_gpu(H, wl, inputs)
+        for k in KEYS:
+            e = rel_err(got[k], rec[k])
+            print(f"  {k}: stash against recompute {e:.2e}", flush=True)
+            assert e <= 2e-5, k
     tm = db.tanh_map.view(wl.B, wl.Tq, wl.Tk, wl.H)
     for b in (0, wl.B - 1):
         L = int(inputs["key_len"][b])
-        want = np.tanh(inputs["Qp"][b].astype(np.float64)[:, None, :] + inputs["Kp"][b, :L].astype(np.float64)[None])
-        assert np.abs(tm[b, :, :L].cpu().numpy() - want).max() < 5e-7
+        rows = range(wl.Tq) if idx <= 1 else (0, wl.Tq // 2, wl.Tq - 1)
+        for i in rows:
+            want = np.tanh(inputs["Qp"][b, i].astype(np.float64)[None, :] + inputs["Kp"][b, :L].astype(np.float64))
+            assert np.abs(tm[b, i, :L].cpu().numpy() - want).max() < 5e-7
 
 
 def test_forward_only_and_backward_from_given_P(H):
