@@ -295,6 +295,7 @@ STEP_CASES = [
     ("steps_64_keys_ragged_second_chunk", 5, 3, 64, 260, 264, "f32"),      # the short-axis kernels at their limit
     ("steps_65_keys", 3, 2, 65, 64, 32, "bf16"),                           # one key beyond it
     ("steps_with_empty_samples", 9, 2, 6, 32, 16, "f32"),                  # key_len drawn from 0..Tk
+    ("steps_batch_beyond_the_four_block_form", 70, 2, 20, 64, 32, "f32"),  # 4 B blocks would not all run at once
 ]
 
 
