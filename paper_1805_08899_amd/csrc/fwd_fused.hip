@@ -328,6 +328,127 @@ __device__ __forceinline__ bool fw_rows_n(int nk, const float4 (&raw)[NS][NKM], 
     return false;                            // nk == 0: nothing to do
 }
 
+// Context rows = P V on the matrix cores.  One 4x4x1 MFMA multiplies 4 rows of P (replicated over the 16 lane
+// groups) with one V value per lane, so a lane owns an output column; with CPL > 1 a lane owns CPL neighbouring
+// columns, loaded in one 8- or 16-byte piece and fed to CPL products, and a wave takes 64 CPL columns at a time.
+// The batches of value rows of all of a wave's column groups form one sequence; the loads of the next batch are
+// issued before the current one is multiplied.  Keys past L carry P = 0, the last valid row stands in for them;
+// no branches around the loads, so that they stay in flight across the arithmetic of the batch before.
+template <int CPL> struct ColVec;
+template <> struct ColVec<1> {
+    static __device__ __forceinline__ void load(const float *p, size_t i, float (&d)[1]) { d[0] = p[i]; }
+    static __device__ __forceinline__ void load(const bf16_t *p, size_t i, float (&d)[1]) { d[0] = ld(p, i); }
+    static __device__ __forceinline__ void store(float *p, const float (&x)[1]) { store_streaming(p, x[0]); }
+};
+template <> struct ColVec<2> {
+    static __device__ __forceinline__ void load(const float *p, size_t i, float (&d)[2]) {
+        const float2 x = *reinterpret_cast<const float2 *>(p + i);
+        d[0] = x.x;
+        d[1] = x.y;
+    }
+    static __device__ __forceinline__ void load(const bf16_t *p, size_t i, float (&d)[2]) {
+        const uint32_t u = *reinterpret_cast<const uint32_t *>(p + i);
+        d[0] = __uint_as_float(u << 16);
+        d[1] = __uint_as_float(u & 0xffff0000u);
+    }
+    static __device__ __forceinline__ void store(float *p, const float (&x)[2]) {
+        typedef float f2 __attribute__((ext_vector_type(2)));
+        __builtin_nontemporal_store((f2){x[0], x[1]}, reinterpret_cast<f2 *>(p));
+    }
+};
+template <> struct ColVec<4> {
+    template <typename T> static __device__ __forceinline__ void load(const T *p, size_t i, float (&d)[4]) {
+        const float4 x = ld4(p, i);
+        d[0] = x.x;
+        d[1] = x.y;
+        d[2] = x.z;
+        d[3] = x.w;
+    }
+    static __device__ __forceinline__ void store(float *p, const float (&x)[4]) {
+        store4_streaming(p, make_float4(x[0], x[1], x[2], x[3]));
+    }
+};
+
+template <typename T, int RT, int CPL>
+struct ContextPhase {
+    static constexpr int KB = CPL == 4 ? 8 : FW_KB;     // value rows per batch (two batches in flight per wave)
+    static constexpr int NR4 = RT / 4;
+    float vcur[KB][CPL], vnxt[KB][CPL];
+
+    // rows kb0 .. kb0 + KB - 1 of column group g
+    __device__ __forceinline__ void fetch(float (&dst)[KB][CPL], const T *vb, int Dv, int L, int lane, int g, int kb0) {
+        const int n = min((g * 64 + lane) * CPL, Dv - CPL);
+#pragma unroll
+        for (int kk = 0; kk < KB; ++kk)
+            ColVec<CPL>::load(vb, (size_t)(unsigned)(min(kb0 + kk, L - 1) * Dv + n), dst[kk]);
+    }
+    __device__ __forceinline__ void start(const T *vb, int Dv, int L, int lane, int w) {
+        const int n_grp = (Dv + 64 * CPL - 1) / (64 * CPL);
+        fetch(vcur, vb, Dv, L, lane, min(w, n_grp - 1), 0);
+    }
+    __device__ __forceinline__ void run(const T *vb, const float *s_S, int spitch, float *Cb, int Dv, int L, int Lp,
+                                        int ni, int lane, int w) {
+        const int n_grp = (Dv + 64 * CPL - 1) / (64 * CPL);
+        const int lr = lane & 3;
+        f32x4 acc[CPL][NR4];
+#pragma unroll
+        for (int c = 0; c < CPL; ++c)
+#pragma unroll
+            for (int t = 0; t < NR4; ++t) acc[c][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        int g = w, kb0 = 0;
+        while (g < n_grp) {
+            int g2 = g, kb2 = kb0 + KB;
+            if (kb2 >= Lp) {
+                g2 = g + FW_W;
+                kb2 = 0;
+            }
+            fetch(vnxt, vb, Dv, L, lane, min(g2, n_grp - 1), kb2);
+#pragma unroll
+            for (int k4 = 0; k4 < KB; k4 += 4) {
+                if (kb0 + k4 < Lp) {
+                    float4 pr[NR4];
+#pragma unroll
+                    for (int t = 0; t < NR4; ++t)
+                        pr[t] = *reinterpret_cast<const float4 *>(s_S + (4 * t + lr) * spitch + kb0 + k4);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+#pragma unroll
+                        for (int c = 0; c < CPL; ++c)
+#pragma unroll
+                            for (int t = 0; t < NR4; ++t)
+                                acc[c][t] = __builtin_amdgcn_mfma_f32_4x4x1f32(comp(pr[t], q), vcur[k4 + q][c],
+                                                                               acc[c][t], 0, 0, 0);
+                }
+            }
+            if (kb2 == 0) {                                        // last batch of column group g
+                const int n = (g * 64 + lane) * CPL;
+                if (n < Dv) {
+#pragma unroll
+                    for (int t = 0; t < NR4; ++t)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            if (4 * t + r < ni) {
+                                float x[CPL];
+#pragma unroll
+                                for (int c = 0; c < CPL; ++c) x[c] = acc[c][t][r];
+                                ColVec<CPL>::store(&Cb[(size_t)(4 * t + r) * Dv + n], x);
+                            }
+                }
+#pragma unroll
+                for (int c = 0; c < CPL; ++c)
+#pragma unroll
+                    for (int t = 0; t < NR4; ++t) acc[c][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int kk = 0; kk < KB; ++kk)
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) vcur[kk][c] = vnxt[kk][c];
+            g = g2;
+            kb0 = kb2;
+        }
+    }
+};
+
 // Which (sample, row tile) this block works on and the sample's valid keys; see "Placement" at the top.
 // Ranked mode: wave 0 finds the sample that holds a given rank by radix selection over composite keys
 // (valid keys, then index) held two per lane, and hands the answer to the other waves through s_pick.
@@ -557,94 +678,53 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
     }
     __builtin_amdgcn_s_setprio(3);
 
-    // first batch of value rows for the context phase leaves before the softmax
+    // ---- C and D: softmax, then context rows = P V; the first batch of value rows leaves before the softmax.
+    // Wide value rows take two or four columns per lane (8- or 16-byte loads).
     const T *vb = V + (size_t)b * Tk * Dv;
     const int Lp = (L + 3) & ~3;
-    const int n_grp = (Dv + 63) / 64;
-    float vcur[FW_KB], vnxt[FW_KB];
-    // rows kb0 .. kb0 + FW_KB - 1 of column group g; keys past L carry P = 0, the last valid row stands in for
-    // them; no branches, so that the loads stay in flight across the arithmetic of the batch before
-    auto v_fetch = [&](float (&dst)[FW_KB], int g, int kb0) {
-        const int n = min(g * 64 + lane, Dv - 1);
-#pragma unroll
-        for (int kk = 0; kk < FW_KB; ++kk) dst[kk] = ld(vb, (size_t)(unsigned)(min(kb0 + kk, L - 1) * Dv + n));
+    auto softmax = [&]() {
+        lds_barrier();
+        // waves take rows in turn; probabilities replace the scores in LDS
+        for (int a = w; a < RT; a += FW_W) {
+            float *srow = s_S + a * spitch;
+            if (a < ni) {
+                float m = -INFINITY;
+                for (int j = lane; j < L; j += 64) m = fmaxf(m, srow[j]);
+                m = wave_max(m);
+                float z = 0.f;
+                for (int j = lane; j < L; j += 64) {
+                    const float e = fast_exp2((srow[j] - m) * 1.4426950408889634f);
+                    srow[j] = e;
+                    z += e;
+                }
+                z = wave_sum(z);
+                const float inv = 1.0f / z;
+                for (int j = lane; j < max(Tk, Lp); j += 64) {
+                    const float p = j < L ? srow[j] * inv : 0.f;
+                    if (j < Lp) srow[j] = p;
+                    if (j < Tk) store_streaming(&Pb[(size_t)a * Tk + j], p);
+                }
+            } else {
+                for (int j = lane; j < Lp; j += 64) srow[j] = 0.f;
+            }
+        }
+        lds_barrier();
     };
-    v_fetch(vcur, min(w, n_grp - 1), 0);
-    lds_barrier();
-
-    // ---- C: softmax, waves take rows in turn; probabilities replace the scores in LDS
-    for (int a = w; a < RT; a += FW_W) {
-        float *srow = s_S + a * spitch;
-        if (a < ni) {
-            float m = -INFINITY;
-            for (int j = lane; j < L; j += 64) m = fmaxf(m, srow[j]);
-            m = wave_max(m);
-            float z = 0.f;
-            for (int j = lane; j < L; j += 64) {
-                const float e = fast_exp2((srow[j] - m) * 1.4426950408889634f);
-                srow[j] = e;
-                z += e;
-            }
-            z = wave_sum(z);
-            const float inv = 1.0f / z;
-            for (int j = lane; j < max(Tk, Lp); j += 64) {
-                const float p = j < L ? srow[j] * inv : 0.f;
-                if (j < Lp) srow[j] = p;
-                if (j < Tk) store_streaming(&Pb[(size_t)a * Tk + j], p);
-            }
-        } else {
-            for (int j = lane; j < Lp; j += 64) srow[j] = 0.f;
-        }
-    }
-    lds_barrier();
-
-    // ---- D: context rows = P V.  A wave takes 64 columns at a time; lane l owns column n0 + l.
-    // One 4x4x1 MFMA multiplies 4 rows of P (replicated over the 16 lane groups) with one V value per lane.
-    // The batches of value rows of all of a wave's column groups form one sequence; the loads of the next
-    // batch are issued before the current one is multiplied.
-    const int lr = lane & 3;
-    constexpr int NR4 = RT / 4;
-    f32x4 acc[NR4];
-#pragma unroll
-    for (int t = 0; t < NR4; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    int g = w, kb0 = 0;
-    while (g < n_grp) {
-        int g2 = g, kb2 = kb0 + FW_KB;
-        if (kb2 >= Lp) {
-            g2 = g + FW_W;
-            kb2 = 0;
-        }
-        v_fetch(vnxt, min(g2, n_grp - 1), kb2);
-#pragma unroll
-        for (int k4 = 0; k4 < FW_KB; k4 += 4) {
-            if (kb0 + k4 < Lp) {
-                float4 pr[NR4];
-#pragma unroll
-                for (int t = 0; t < NR4; ++t)
-                    pr[t] = *reinterpret_cast<const float4 *>(s_S + (4 * t + lr) * spitch + kb0 + k4);
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-#pragma unroll
-                    for (int t = 0; t < NR4; ++t)
-                        acc[t] = __builtin_amdgcn_mfma_f32_4x4x1f32(comp(pr[t], q), vcur[k4 + q], acc[t], 0, 0, 0);
-            }
-        }
-        if (kb2 == 0) {                                        // last batch of column group g
-            const int n = g * 64 + lane;
-            if (n < Dv) {
-#pragma unroll
-                for (int t = 0; t < NR4; ++t)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        if (4 * t + r < ni) store_streaming(&Cb[(size_t)(4 * t + r) * Dv + n], acc[t][r]);
-            }
-#pragma unroll
-            for (int t = 0; t < NR4; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
-        }
-#pragma unroll
-        for (int kk = 0; kk < FW_KB; ++kk) vcur[kk] = vnxt[kk];
-        g = g2;
-        kb0 = kb2;
+    if (Dv >= 1024) {                                           // at least four waves with columns to work on
+        ContextPhase<T, RT, 4> cp;
+        cp.start(vb, Dv, L, lane, w);
+        softmax();
+        cp.run(vb, s_S, spitch, Cb, Dv, L, Lp, ni, lane, w);
+    } else if (Dv >= 512) {
+        ContextPhase<T, RT, 2> cp;
+        cp.start(vb, Dv, L, lane, w);
+        softmax();
+        cp.run(vb, s_S, spitch, Cb, Dv, L, Lp, ni, lane, w);
+    } else {
+        ContextPhase<T, RT, 1> cp;
+        cp.start(vb, Dv, L, lane, w);
+        softmax();
+        cp.run(vb, s_S, spitch, Cb, Dv, L, Lp, ni, lane, w);
     }
 }
 
