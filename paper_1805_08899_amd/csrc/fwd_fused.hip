@@ -118,7 +118,9 @@ struct KeyStream {
         NS = NS_;
         npass = (nk + FW_NJ - 1) / FW_NJ;
         const int np = max(npass, 1);
-        base = nk / np;
+        // the same in all lanes, but the division runs on the vector unit: back to scalar registers, so that
+        // everything derived from it (pass bounds, row addresses) is scalar arithmetic
+        base = __builtin_amdgcn_readfirstlane(nk / np);
         extra = nk - base * np;
         p_f = 0;
         s_f = 0;
@@ -129,15 +131,20 @@ struct KeyStream {
     // which exists because the block has at least one valid key), so the loads in flight never meet a
     // control-flow join and stay in flight while the previous slice is being evaluated.
     __device__ __forceinline__ void fetch() {
+        // the stream position is the same in all lanes; taken through scalar registers so that the pass bounds
+        // and row addresses below are scalar arithmetic (the compiler otherwise carries them per lane)
+        p_f = __builtin_amdgcn_readfirstlane(p_f);
+        s_f = __builtin_amdgcn_readfirstlane(s_f);
         const int pc = min(p_f, max(npass, 1) - 1);
         const int j0 = pass_begin(pc), j1 = max(pass_begin(pc + 1), j0 + 1);
         // columns past H: the load repeats the row's last four values; exp(2q)/v is 0 and 1/v is kHugeC
         // there, so they add nothing
-        const int hc = min(s_f * FW_SS + lane4, H - 4);
+        const unsigned hc = (unsigned)min(s_f * FW_SS + lane4, H - 4);
 #pragma unroll
         for (int c = 0; c < FW_NJ; ++c) {
-            const int j = min(j0 + c, j1 - 1);
-            cur[c] = ld4(kb, (size_t)(unsigned)(j * H + hc));
+            // row address from scalars, column from the lane: the load takes them as base and offset
+            const T *row = kb + (size_t)(unsigned)(min(j0 + c, j1 - 1) * H);
+            cur[c] = ld4(row, (size_t)hc);
         }
         const bool wrap = s_f + 1 == NS;
         s_f = wrap ? 0 : s_f + 1;
