@@ -230,8 +230,9 @@ def main() -> int:
     wl_dec = WORKLOADS[1]
     decoder = decoder_steps(eb, harness, torch, wl_dec, inputs if wl is wl_dec else make_inputs(wl_dec), dev,
                             cpu=cpu if wl is wl_dec else None) if extras else None
-    dropout = dropout_codec(eb, torch, dev, cpu=not args.no_cpu_baseline) if extras else None
-    lstm = lstm_cell(eb, torch, dev, cpu=not args.no_cpu_baseline) if extras else None
+    copy_big = cal.get("copy_beyond_cache_read_plus_write_bytes_per_s")
+    dropout = dropout_codec(eb, torch, dev, cpu=not args.no_cpu_baseline, copy_rate=copy_big) if extras else None
+    lstm = lstm_cell(eb, torch, dev, cpu=not args.no_cpu_baseline, copy_rate=copy_big) if extras else None
 
     out = {
         "metric": "attention fwd+bwd calls/s",
@@ -293,6 +294,15 @@ def calibrate(eb, torch, dev):
     src = torch.empty(n, dtype=torch.uint8, device=dev)
     dst = torch.empty(n, dtype=torch.uint8, device=dev)
     out["copy_read_plus_write_bytes_per_s"] = 2 * run(eb.ECHO_CAL_COPY, src=src, dst=dst, nbytes=n)
+    del src, dst
+    # The 256 MiB copy above runs out of the 256 MB on-die cache behind the L2s and reads more than the 8 TB/s of
+    # the HBM; a copy of 1 GiB each way does not fit there and shows what the memory itself delivers to a plain
+    # two-stream copy (about 5 TB/s).  The streaming rows below (dropout codec, LSTM block at 16384 x 1024) move
+    # 0.5 to 1 GB per launch and are to be read against this figure as well as against the published peak.
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device=dev)
+    dst = torch.empty(n, dtype=torch.uint8, device=dev)
+    out["copy_beyond_cache_read_plus_write_bytes_per_s"] = 2 * run(eb.ECHO_CAL_COPY, src=src, dst=dst, nbytes=n)
     return out
 
 
@@ -413,7 +423,7 @@ def decoder_steps(eb, harness, torch, wl, inputs, dev, reps=20, cpu=None):
     return out
 
 
-def dropout_codec(eb, torch, dev, n=1 << 26, p=0.1, reps=20, cpu=True):
+def dropout_codec(eb, torch, dev, n=1 << 26, p=0.1, reps=20, cpu=True, copy_rate=None):
     """One-bit dropout on n fp32 elements: forward reads x and writes y plus n/8 bytes of mask, backward reads dy
     and the mask and writes dx: 8.125 algorithmic bytes per element and pass, against the 8 TB/s HBM peak."""
     x = torch.randn(n, device=dev)
@@ -438,8 +448,10 @@ def dropout_codec(eb, torch, dev, n=1 << 26, p=0.1, reps=20, cpu=True):
     t_b = timed(lambda: eb.check(eb.echo_dropout_bwd(y, bits, n, p, dx, stream=st), "echo_dropout_bwd"))
     nbytes = 8.125 * n
     out = {"elements": n, "p": p, "bytes_per_element_and_pass": 8.125,
-           "fwd": {"ms": t_f * 1e3, "GB_per_s": nbytes / t_f / 1e9, "frac_of_8TBps": nbytes / t_f / PEAK_HBM},
-           "bwd": {"ms": t_b * 1e3, "GB_per_s": nbytes / t_b / 1e9, "frac_of_8TBps": nbytes / t_b / PEAK_HBM},
+           "fwd": {"ms": t_f * 1e3, "GB_per_s": nbytes / t_f / 1e9, "frac_of_8TBps": nbytes / t_f / PEAK_HBM,
+                   "vs_copy_beyond_cache": nbytes / t_f / copy_rate if copy_rate else None},
+           "bwd": {"ms": t_b * 1e3, "GB_per_s": nbytes / t_b / 1e9, "frac_of_8TBps": nbytes / t_b / PEAK_HBM,
+                   "vs_copy_beyond_cache": nbytes / t_b / copy_rate if copy_rate else None},
            "feature_map_bytes": {"one_bit": n // 8, "fp32_mask": 4 * n}}
     if cpu:
         import numpy as np
@@ -456,7 +468,7 @@ def dropout_codec(eb, torch, dev, n=1 << 26, p=0.1, reps=20, cpu=True):
     return out
 
 
-def lstm_cell(eb, torch, dev, shapes=((128, 512), (128, 1024), (16384, 1024)), reps=50, cpu=True):
+def lstm_cell(eb, torch, dev, shapes=((128, 512), (128, 1024), (16384, 1024)), reps=50, cpu=True, copy_rate=None):
     """The LSTM cell's non-linear block.  Algorithmic bytes per element of [B, H]: recompute forward 60 (reads
     Gx, Gh, c_prev, writes h, c and the kept sum), recompute backward 48 (reads dh, dc, the sum, c_prev, writes
     da, dc_prev); stash forward 64, stash backward 52.  The first two shapes are one cell of the translation
@@ -502,6 +514,8 @@ def lstm_cell(eb, torch, dev, shapes=((128, 512), (128, 1024), (16384, 1024)), r
             dt = timed(fn)
             nbytes = out["bytes_per_element"][k] * n
             row[k] = {"us": dt * 1e6, "GB_per_s": nbytes / dt / 1e9, "frac_of_8TBps": nbytes / dt / PEAK_HBM}
+            if copy_rate and nbytes > (256 << 20):     # only launches that do not fit the on-die cache
+                row[k]["vs_copy_beyond_cache"] = nbytes / dt / copy_rate
         out["shapes"].append(row)
         del t, o
     if cpu:
