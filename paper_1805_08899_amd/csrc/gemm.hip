@@ -333,6 +333,100 @@ __device__ __forceinline__ void dscore_block_dsplit(const float *__restrict__ dC
     }
 }
 
+// dV of one sample for a 64-wide group of columns and ALL keys: dV[j, n0 .. n0+63] = sum_i P[i, j] dC[i, n0 ..].
+// The block's slice of dC (Tq rows of 256 bytes) passes through the CU once; the earlier form, a block per 16 keys
+// and 256 columns, read dC once per key tile and was bound by what the L2 could deliver at the larger workloads.
+// Wave w owns key tiles w, w + 4, ... and works on KT of them at a time: per step of four query rows a lane loads
+// KT values of P (one per key tile) and four consecutive columns of dC (one 16-byte load) and issues 4 KT products.
+// Batches of U steps are double buffered: the loads of the next batch are in flight during the products of this one.
+// Rows of masked keys (j >= L) come out as exact zeros.
+template <int KT>
+__device__ __forceinline__ void dv_cols_block(const float *__restrict__ P, const float *__restrict__ dC,
+                                              const int *__restrict__ key_len, float *__restrict__ dV, int Tq, int Tk,
+                                              int Dv, int b, int cg, int acc_out) {
+    constexpr int U = KT == 1 ? 8 : KT == 2 ? 6 : KT == 3 ? 4 : 3;
+    const int L = clamp_len(key_len[b], Tk);
+    const int lane = lane_id(), w = wave_id();
+    const int lm = lane & 15, lk = lane >> 4;
+    const int ncol = cg * 64 + 4 * lm;
+    const bool nok = ncol < Dv;
+    const float *Pb = P + (size_t)b * Tq * Tk;
+    const float *dCb = dC + (size_t)b * Tq * Dv + min(ncol, Dv - 4);
+    float *dVb = dV + (size_t)b * Tk * Dv + ncol;
+    const int n_kt = (Tk + 15) / 16;
+    const int n_steps = (Tq + 3) / 4;
+    for (int jt0 = w; jt0 < n_kt; jt0 += 4 * KT) {                 // this wave's tiles jt0, jt0 + 4, ...
+        int m[KT];                                                  // key of this lane in tile t (clamped for loading)
+#pragma unroll
+        for (int t = 0; t < KT; ++t) m[t] = min((jt0 + 4 * t) * 16 + lm, Tk - 1);
+        f32x4 acc[KT][4];
+#pragma unroll
+        for (int t = 0; t < KT; ++t)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[t][c] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        if (jt0 * 16 < L) {                                         // uniform: else all of the group's keys are masked
+            float a[2][U][KT];
+            float4 bv[2][U];
+            auto load = [&](int buf, int st0) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int kc = min(4 * (st0 + u) + lk, Tq - 1);
+#pragma unroll
+                    for (int t = 0; t < KT; ++t) a[buf][u][t] = Pb[(size_t)kc * Tk + m[t]];
+                    bv[buf][u] = ld4(dCb, (size_t)kc * Dv);
+                }
+            };
+            auto mult = [&](int buf, int st0) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (st0 + u < n_steps) {                        // uniform
+                        // query rows past Tq (last step only) were loaded from row Tq - 1: they add nothing.
+                        // Masked here, at the point of use, so that nothing waits for the loads earlier.
+                        const bool kv = 4 * (st0 + u) + lk < Tq;
+#pragma unroll
+                        for (int t = 0; t < KT; ++t) {
+                            const float av = kv ? a[buf][u][t] : 0.f;
+                            acc[t][0] = mfma16(av, bv[buf][u].x, acc[t][0]);
+                            acc[t][1] = mfma16(av, bv[buf][u].y, acc[t][1]);
+                            acc[t][2] = mfma16(av, bv[buf][u].z, acc[t][2]);
+                            acc[t][3] = mfma16(av, bv[buf][u].w, acc[t][3]);
+                        }
+                    }
+                }
+            };
+            load(0, 0);
+            for (int st0 = 0; st0 < n_steps; st0 += 2 * U) {
+                if (st0 + U < n_steps) load(1, st0 + U);
+                mult(0, st0);
+                if (st0 + 2 * U < n_steps) load(0, st0 + 2 * U);
+                if (st0 + U < n_steps) mult(1, st0 + U);
+            }
+        }
+        if (nok) {
+#pragma unroll
+            for (int t = 0; t < KT; ++t) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int j = (jt0 + 4 * t) * 16 + 4 * lk + r;
+                    if (j < Tk) {
+                        float4 o = make_float4(acc[t][0][r], acc[t][1][r], acc[t][2][r], acc[t][3][r]);
+                        if (j >= L) o = make_float4(0.f, 0.f, 0.f, 0.f);      // masked key: its P column was not zeroed above
+                        float *dst = dVb + (size_t)j * Dv;
+                        if (acc_out) {                               // add to what the earlier decoder steps left
+                            const float4 old = *reinterpret_cast<const float4 *>(dst);
+                            o.x += old.x;
+                            o.y += old.y;
+                            o.z += old.z;
+                            o.w += old.w;
+                        }
+                        store4_streaming(dst, o);
+                    }
+                }
+            }
+        }
+    }
+}
+
 // For the recompute kernel: order[r] = b | L_b << 16 for the sample b with the
 // r-th most valid keys (ties by index), or r-th in index order when `sorted` is 0.  With `fold` the second
 // half runs lightest first: when the whole recompute grid is resident at once,
@@ -361,13 +455,13 @@ __device__ __forceinline__ void rank_block(const int *__restrict__ key_len, int 
 // Everything the backward pass needs before the recomputation, in one launch:
 // blocks that produce dS (B1 + B2), blocks that produce dV (B1) and one block
 // that ranks the samples.  The three kinds of block do not depend on each other.
-template <typename TV>
+template <typename TV, int KT>
 __global__ __launch_bounds__(256, 3) void k_bwd_pre(const float *__restrict__ dC, const TV *__restrict__ V,
                                                  const float *__restrict__ P, const int *__restrict__ key_len,
                                                  float *__restrict__ dS, float *__restrict__ ds_rowsum,
                                                  int *__restrict__ order, float *__restrict__ dV, int B, int sorted,
                                                  int fold,
-                                                 int Tq, int Tk, int Dv, int pitch, int s_tiles, int v_xt, int v_yt, int acc) {
+                                                 int Tq, int Tk, int Dv, int pitch, int s_tiles, int v_groups, int acc) {
     extern __shared__ float s_dp[];           // [16][pitch16], four such planes when Tk <= kDsplitMaxTk
     __shared__ int s_len[kMaxSortedB];
     // The hardware deals blocks to the eight XCDs round-robin, so block id mod 8 names the XCD.  Sample b is
@@ -375,7 +469,7 @@ __global__ __launch_bounds__(256, 3) void k_bwd_pre(const float *__restrict__ dC
     // long dS blocks of all its samples come first, then the dV blocks; the last block of the grid ranks.
     constexpr int kXcd = 8;
     const int spx = (B + kXcd - 1) / kXcd;                     // sample slots per XCD
-    const int per_b = v_xt * v_yt;
+    const int per_b = v_groups;                               // dV blocks per sample: one per 64 columns
     const int per_xcd = spx * (s_tiles + per_b);
     if ((int)blockIdx.x == kXcd * per_xcd) {
         rank_block(key_len, order, s_len, B, Tk, sorted, fold);
@@ -395,7 +489,12 @@ __global__ __launch_bounds__(256, 3) void k_bwd_pre(const float *__restrict__ dC
     li -= spx * s_tiles;
     const int b = xcd + kXcd * (li / per_b), rem = li % per_b;
     if (b >= B) return;
-    pv_block<float, true>(P, dC, key_len, dV, Tq, Tk, Dv, b, rem / v_xt, rem % v_xt, acc);
+    if constexpr (KT > 0) {
+        dv_cols_block<KT>(P, dC, key_len, dV, Tq, Tk, Dv, b, rem, acc);
+    } else {                                  // v_groups = column groups of 256, times the key tiles
+        const int v_xt = (Dv + 255) / 256;
+        pv_block<float, true>(P, dC, key_len, dV, Tq, Tk, Dv, b, rem / v_xt, rem % v_xt, acc);
+    }
 }
 
 hipError_t launch_bwd_pre(const AttnShape &s, const float *dC, const void *V, const float *P, const int *key_len,
@@ -404,25 +503,40 @@ hipError_t launch_bwd_pre(const AttnShape &s, const float *dC, const void *V, co
     const int n_hs = (s.H + 63) / 64;
     const int fold = (sorted && (long long)s.B * n_hs <= 512) ? 1 : 0;   // recompute grid in one round
     const int s_tiles = with_ds ? (s.Tq + 15) / 16 : 0;
-    const int v_xt = (s.Dv + 255) / 256, v_yt = (s.Tk + 15) / 16;
-    const long long blocks = 1 + 8LL * ((s.B + 7) / 8) * (s_tiles + (long long)v_xt * v_yt);
+    // dV blocks per sample.  Short key axes (at most four key tiles, one per wave): a block owns 64 columns and all
+    // keys, so its slice of dC is read once (dv_cols_block).  Longer key axes: a block per 16 keys and 256 columns
+    // (pv_block); there the all-keys form was measured slower (3 to 12 % of this kernel at workloads 2 and 3: fewer,
+    // longer blocks balance worse and a wave's batches of loads are too short to cover a trip to memory).
+    const int per_wave = ((s.Tk + 15) / 16 + 3) / 4;
+    const int kt = per_wave <= 1 ? 1 : 0;
+    const int v_groups = kt ? (s.Dv + 63) / 64 : ((s.Dv + 255) / 256) * ((s.Tk + 15) / 16);
+    const long long blocks = 1 + 8LL * ((s.B + 7) / 8) * (s_tiles + (long long)v_groups);
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     const int pitch16 = (s.Tk + 15) / 16 * 16 + 4;
     const size_t lds = (size_t)(s.Tk <= kDsplitMaxTk ? 4 : 1) * 16 * pitch16 * sizeof(float);
-    if (lds > 48 * 1024) {   // beyond the default dynamic LDS limit (up to 160 KB per block on gfx950)
-        static LdsGrants granted_bf16, granted_f32;
-        hipError_t e = s.bf16 ? ensure_dynamic_lds((const void *)k_bwd_pre<bf16_t>, lds, granted_bf16)
-                              : ensure_dynamic_lds((const void *)k_bwd_pre<float>, lds, granted_f32);
-        if (e != hipSuccess) return e;
+#define ECHO_PRE_LAUNCH(TV, KT)                                                                                     \
+    do {                                                                                                            \
+        if (lds > 48 * 1024) { /* beyond the default dynamic LDS limit (up to 160 KB per block on gfx950) */        \
+            static LdsGrants granted;                                                                               \
+            hipError_t e = ensure_dynamic_lds((const void *)k_bwd_pre<TV, KT>, lds, granted);                       \
+            if (e != hipSuccess) return e;                                                                          \
+        }                                                                                                           \
+        k_bwd_pre<TV, KT><<<(unsigned)blocks, 256, lds, st>>>(dC, (const TV *)V, P, key_len, dS, ds_rowsum, order, dV, \
+                                                             s.B, sorted, fold, s.Tq, s.Tk, s.Dv, ds_pitch(s.Tk),  \
+                                                             s_tiles, v_groups, s.acc ? 1 : 0);                     \
+    } while (0)
+#define ECHO_PRE_KT(TV)                                 \
+    switch (kt) {                                       \
+        case 1: ECHO_PRE_LAUNCH(TV, 1); break;          \
+        default: ECHO_PRE_LAUNCH(TV, 0); break;         \
     }
-    if (s.bf16)
-        k_bwd_pre<bf16_t><<<(unsigned)blocks, 256, lds, st>>>(dC, (const bf16_t *)V, P, key_len, dS, ds_rowsum, order,
-                                                             dV, s.B, sorted, fold, s.Tq, s.Tk, s.Dv,
-                                                             ds_pitch(s.Tk), s_tiles, v_xt, v_yt, s.acc ? 1 : 0);
-    else
-        k_bwd_pre<float><<<(unsigned)blocks, 256, lds, st>>>(dC, (const float *)V, P, key_len, dS, ds_rowsum, order,
-                                                            dV, s.B, sorted, fold, s.Tq, s.Tk, s.Dv,
-                                                            ds_pitch(s.Tk), s_tiles, v_xt, v_yt, s.acc ? 1 : 0);
+    if (s.bf16) {
+        ECHO_PRE_KT(bf16_t)
+    } else {
+        ECHO_PRE_KT(float)
+    }
+#undef ECHO_PRE_KT
+#undef ECHO_PRE_LAUNCH
     return hipGetLastError();
 }
 
