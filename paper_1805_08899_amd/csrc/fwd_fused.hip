@@ -43,8 +43,10 @@ namespace echo {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 
-constexpr int FW_W = 8;          // waves per block (deal8_begin deals the keys to eight)
-constexpr int FW_THREADS = 64 * FW_W;
+constexpr int FW_W = 8;          // waves per block in row mode (deal8_begin deals the keys to eight)
+constexpr int FW_W_STREAM = 4;   // waves per block in streaming mode when H <= 512: four blocks per CU instead of
+                                 // two, so that more blocks are in different phases at any time (placement, staging,
+                                 // softmax and context wait on memory; only the score loop fills the vector units)
 constexpr int FW_NJ = 4;         // keys per wave and pass (register tile columns)
 constexpr int FW_SS = 256;       // h per slice: four per lane
 constexpr int FW_XCD = 8;        // blockIdx.x mod 8 selects the XCD
@@ -394,7 +396,7 @@ struct ContextPhase {
         fetch(vcur, vb, Dv, L, lane, min(w, n_grp - 1), 0);
     }
     __device__ __forceinline__ void run(const T *vb, const float *s_S, int spitch, float *Cb, int Dv, int L, int Lp,
-                                        int ni, int lane, int w) {
+                                        int ni, int lane, int w, int n_waves) {
         const int n_grp = (Dv + 64 * CPL - 1) / (64 * CPL);
         const int lr = lane & 3;
         f32x4 acc[CPL][NR4];
@@ -406,7 +408,7 @@ struct ContextPhase {
         while (g < n_grp) {
             int g2 = g, kb2 = kb0 + KB;
             if (kb2 >= Lp) {
-                g2 = g + FW_W;
+                g2 = g + n_waves;
                 kb2 = 0;
             }
             fetch(vnxt, vb, Dv, L, lane, min(g2, n_grp - 1), kb2);
@@ -520,19 +522,27 @@ __device__ __forceinline__ bool fw_pick_item(const int *__restrict__ key_len, in
     return true;
 }
 
-template <typename T, int NG, int ROWNS>
-__global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
+// items dealt to the W waves of a block as contiguous ranges: first item of wave w (w = W gives n)
+template <int W> __device__ __forceinline__ int deal_begin(int n, int w) {
+    if constexpr (W == 8) return deal8_begin(n, w);
+    else return (int)((unsigned)(n * w) / (unsigned)W);
+}
+
+template <typename T, int NG, int ROWNS, int W>
+__global__ __launch_bounds__(64 * W, NG == 1 ? 4 : 2) void k_fwd_fused(
     const T *__restrict__ Qp, const T *__restrict__ Kp, const T *__restrict__ V, const T *__restrict__ v,
     const int *__restrict__ key_len, float *__restrict__ C, float *__restrict__ P,
     int B, int Tq, int Tk, int H, int Dv, int tiles, int Hp, int spitch, int ranked) {
     constexpr int RT = 8 * NG;
+    constexpr int FW_THREADS = 64 * W;
+    constexpr int NB = 32 / W;                                 // 16-byte pieces per thread and staging batch
     constexpr bool ROWMODE = ROWNS > 0;                       // ROWNS: slices of h in row mode, 0 = streaming mode
     constexpr int NKM = fw_row_max_keys(ROWNS);
     extern __shared__ __align__(16) float smem[];
     float *s_e = smem;                       // [RT][Hp]  exp(2q) / v
     float *s_c = s_e + RT * Hp;              // [Hp]      1 / v
     float *s_S = s_c + Hp;                   // [RT][spitch]  scores, then probabilities
-    __shared__ float s_red[2 * FW_W];
+    __shared__ float s_red[2 * W];
 
     const int lane = lane_id(), w = wave_id();
     // Two blocks share a CU and reach their phases at different times.  The short phases that wait on memory
@@ -544,10 +554,10 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
     // v does not depend on the placement: the first batch of its loads leaves before the key counts are read
     // (in wave 0, which reads the key counts and must not queue them behind anything, right after that)
     const int q4 = Hp / 4;                                    // 16-byte columns per row
-    float4 vv[4];
+    float4 vv[NB];
     auto load_v = [&]() {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < NB; ++u) {
             const int e = threadIdx.x + u * FW_THREADS;
             const int h = 4 * (e % q4);
             vv[u] = (e < RT * q4 && h < H) ? ld4(v, (size_t)h) : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -578,15 +588,15 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
     // mode: the first slice); then A: exp(2q)/v and 1/v to LDS (rows past ni and columns past H: 0 and kHugeC)
     const T *qb = Qp + ((size_t)b * Tq + r0) * H;
     const T *kb = Kp + (size_t)b * Tk * H;
-    float4 x[4];
+    float4 x[NB];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < NB; ++u) {
         const int e = threadIdx.x + u * FW_THREADS;
         const int a = e / q4, h = 4 * (e % q4);
         x[u] = (e < RT * q4 && h < H && a < ni) ? ld4(qb, (size_t)a * H + h) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
-    const int k_lo = deal8_begin(L, w);
-    const int nk = deal8_begin(L, w + 1) - k_lo;
+    const int k_lo = deal_begin<W>(L, w);
+    const int nk = deal_begin<W>(L, w + 1) - k_lo;
     KeyStream<T> ks;
     float4 raw[ROWMODE ? ROWNS : 1][NKM];
     if constexpr (ROWMODE) {
@@ -611,10 +621,10 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
     }
 
     float qe_m = 0.f, c_m = 0.f;
-    for (int e0 = threadIdx.x; e0 < RT * q4; e0 += 4 * FW_THREADS) {
+    for (int e0 = threadIdx.x; e0 < RT * q4; e0 += NB * FW_THREADS) {
         if (e0 != (int)threadIdx.x) {                          // later batches (H > 1024): loaded here
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < NB; ++u) {
                 const int e = e0 + u * FW_THREADS;
                 const int a = e / q4, h = 4 * (e % q4);
                 const bool in = e < RT * q4 && h < H;
@@ -623,7 +633,7 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
             }
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < NB; ++u) {
             const int e = e0 + u * FW_THREADS;
             if (e < RT * q4) {
                 const int a = e / q4, h = 4 * (e % q4);
@@ -649,14 +659,14 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
     c_m = wave_max(c_m);
     if (lane == 0) {
         s_red[w] = qe_m;
-        s_red[FW_W + w] = c_m;
+        s_red[W + w] = c_m;
     }
     lds_barrier();
     float qe_max = 0.f, c_max = 0.f;
 #pragma unroll
-    for (int k = 0; k < FW_W; ++k) {
+    for (int k = 0; k < W; ++k) {
         qe_max = fmaxf(qe_max, s_red[k]);
-        c_max = fmaxf(c_max, s_red[FW_W + k]);
+        c_max = fmaxf(c_max, s_red[W + k]);
     }
 
     // ---- B: scores of this wave's keys
@@ -692,7 +702,7 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
     auto softmax = [&]() {
         lds_barrier();
         // waves take rows in turn; probabilities replace the scores in LDS
-        for (int a = w; a < RT; a += FW_W) {
+        for (int a = w; a < RT; a += W) {
             float *srow = s_S + a * spitch;
             if (a < ni) {
                 float m = -INFINITY;
@@ -721,17 +731,17 @@ __global__ __launch_bounds__(FW_THREADS, NG == 1 ? 4 : 2) void k_fwd_fused(
         ContextPhase<T, RT, 4> cp;
         cp.start(vb, Dv, L, lane, w);
         softmax();
-        cp.run(vb, s_S, spitch, Cb, Dv, L, Lp, ni, lane, w);
+        cp.run(vb, s_S, spitch, Cb, Dv, L, Lp, ni, lane, w, W);
     } else if (Dv >= 512) {
         ContextPhase<T, RT, 2> cp;
         cp.start(vb, Dv, L, lane, w);
         softmax();
-        cp.run(vb, s_S, spitch, Cb, Dv, L, Lp, ni, lane, w);
+        cp.run(vb, s_S, spitch, Cb, Dv, L, Lp, ni, lane, w, W);
     } else {
         ContextPhase<T, RT, 1> cp;
         cp.start(vb, Dv, L, lane, w);
         softmax();
-        cp.run(vb, s_S, spitch, Cb, Dv, L, Lp, ni, lane, w);
+        cp.run(vb, s_S, spitch, Cb, Dv, L, Lp, ni, lane, w, W);
     }
 }
 
@@ -757,7 +767,7 @@ static int fwd_row_mode_slices(const AttnShape &s) {
     return (s.Tk + FW_W - 1) / FW_W <= fw_row_max_keys(ns) ? ns : 0;
 }
 
-template <typename T, int NG, int ROWNS>
+template <typename T, int NG, int ROWNS, int W>
 static hipError_t launch_fwd_fused_t(const AttnShape &s, const void *Qp, const void *Kp, const void *V, const void *v,
                                      const int *key_len, float *C, float *P, hipStream_t st) {
     constexpr int RT = 8 * NG;
@@ -766,7 +776,7 @@ static hipError_t launch_fwd_fused_t(const AttnShape &s, const void *Qp, const v
     const size_t lds = fwd_lds_bytes(s, NG);
     if (lds > 48 * 1024) {   // beyond the default dynamic LDS limit
         static LdsGrants granted;
-        hipError_t e = ensure_dynamic_lds((const void *)k_fwd_fused<T, NG, ROWNS>, lds, granted);
+        hipError_t e = ensure_dynamic_lds((const void *)k_fwd_fused<T, NG, ROWNS, W>, lds, granted);
         if (e != hipSuccess) return e;
     }
     const int tiles = (s.Tq + RT - 1) / RT;
@@ -774,7 +784,7 @@ static hipError_t launch_fwd_fused_t(const AttnShape &s, const void *Qp, const v
     const long long grid = (long long)FW_XCD * samples_per_xcd * tiles;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     const int ranked = s.B <= FW_MAX_RANKED_B ? 1 : 0;
-    k_fwd_fused<T, NG, ROWNS><<<(unsigned)grid, FW_THREADS, lds, st>>>(
+    k_fwd_fused<T, NG, ROWNS, W><<<(unsigned)grid, 64 * W, lds, st>>>(
         (const T *)Qp, (const T *)Kp, (const T *)V, (const T *)v, key_len, C, P, s.B, s.Tq, s.Tk, s.H, s.Dv, tiles, Hp,
         spitch, ranked);
     return hipGetLastError();
@@ -784,11 +794,16 @@ template <typename T>
 static hipError_t launch_fwd_fused_mode(const AttnShape &s, const void *Qp, const void *Kp, const void *V,
                                         const void *v, const int *key_len, float *C, float *P, hipStream_t st) {
     switch (fwd_row_mode_slices(s)) {
-        case 1: return launch_fwd_fused_t<T, 1, 1>(s, Qp, Kp, V, v, key_len, C, P, st);
-        case 2: return launch_fwd_fused_t<T, 1, 2>(s, Qp, Kp, V, v, key_len, C, P, st);
-        case 4: return launch_fwd_fused_t<T, 1, 4>(s, Qp, Kp, V, v, key_len, C, P, st);
-        default: return launch_fwd_fused_t<T, 1, 0>(s, Qp, Kp, V, v, key_len, C, P, st);
+        case 1: return launch_fwd_fused_t<T, 1, 1, FW_W>(s, Qp, Kp, V, v, key_len, C, P, st);
+        case 2: return launch_fwd_fused_t<T, 1, 2, FW_W>(s, Qp, Kp, V, v, key_len, C, P, st);
+        case 4: return launch_fwd_fused_t<T, 1, 4, FW_W>(s, Qp, Kp, V, v, key_len, C, P, st);
+        default: break;
     }
+    // Streaming mode.  Up to two slices of h (H <= 512): blocks of four waves, four of them on a CU (measured 9 %
+    // faster at B = 128, T = 100, H = 512); beyond that the row tile's LDS allows only three such blocks and the
+    // eight-wave block, two per CU, keeps more waves resident (four-wave blocks measured 2 % slower at H = 1024).
+    if (s.H <= 2 * FW_SS) return launch_fwd_fused_t<T, 1, 0, FW_W_STREAM>(s, Qp, Kp, V, v, key_len, C, P, st);
+    return launch_fwd_fused_t<T, 1, 0, FW_W>(s, Qp, Kp, V, v, key_len, C, P, st);
 }
 
 hipError_t launch_fwd_fused(const AttnShape &s, const void *Qp, const void *Kp, const void *V, const void *v,
