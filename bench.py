@@ -40,6 +40,7 @@ SLOTS_UNIT = {"fwd_fused": 6.0, "recompute": 9.0}
 SLOTS_ISSUED = {"fwd_fused": 4.5, "recompute": 9.0}
 CAL_MIX = {"fwd_fused": "fwd_mix_tanh_per_s", "recompute": "bwd_mix_tanh_per_s"}
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
+SPINUP_S = 0.3      # untimed run of the step before the warm-up steps: brings the device to its clocks under load
 
 
 def traffic_from_profile(workload_name, kernel):
@@ -108,6 +109,17 @@ def main() -> int:
         db.fwd()
         db.bwd()
 
+    # The shader clock falls back within milliseconds of idle time (the uploads above are enough) and needs about
+    # 0.1 s of load to return to what it holds in a training loop; a short run (--steps 20 --warmup 5 is 1 ms of
+    # work) would otherwise be timed on the ramp.  So the same step runs untimed for SPINUP_S seconds first; the W
+    # warm-up steps and the K timed steps follow without a pause.
+    t_spin = time.perf_counter()
+    spin_steps = 0
+    while time.perf_counter() - t_spin < SPINUP_S:
+        for _ in range(100):
+            step()
+        spin_steps += 100
+        torch.cuda.synchronize(dev)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize(dev)
@@ -246,6 +258,7 @@ def main() -> int:
         "config": {"workload": wl.name, "B": wl.B, "Tq": wl.Tq, "Tk": wl.Tk, "H": wl.H, "Dv": wl.Dv,
                    "in_dtype": wl.in_dtype, "mean_key_len": float(L.mean())},
         "ms_per_step_events": ms_per_step_events, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
+        "untimed_spinup": {"seconds": SPINUP_S, "steps": spin_steps},
         "ms_per_step_repeats": {"median": repeats[2], "min": repeats[0], "max": repeats[4]},
         "kernels": kernels,
         "roofline": roofline,
