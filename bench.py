@@ -66,6 +66,8 @@ def main() -> int:
     ap.add_argument("--workload", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stash", action="store_true")
+    ap.add_argument("--spinup-s", type=float, default=SPINUP_S,
+                    help="seconds the step runs untimed before the warm-up steps (0 for profiler runs)")
     ap.add_argument("--no-extras", action="store_true",
                     help="leave out the per-step decoder form, the one-bit dropout codec and the LSTM cell block")
     ap.add_argument("--dropout", action="store_true", help="(kept for old command lines; the codec is timed by default)")
@@ -115,7 +117,7 @@ def main() -> int:
     # warm-up steps and the K timed steps follow without a pause.
     t_spin = time.perf_counter()
     spin_steps = 0
-    while time.perf_counter() - t_spin < SPINUP_S:
+    while time.perf_counter() - t_spin < args.spinup_s:
         for _ in range(100):
             step()
         spin_steps += 100
@@ -258,7 +260,7 @@ def main() -> int:
         "config": {"workload": wl.name, "B": wl.B, "Tq": wl.Tq, "Tk": wl.Tk, "H": wl.H, "Dv": wl.Dv,
                    "in_dtype": wl.in_dtype, "mean_key_len": float(L.mean())},
         "ms_per_step_events": ms_per_step_events, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
-        "untimed_spinup": {"seconds": SPINUP_S, "steps": spin_steps},
+        "untimed_spinup": {"seconds": args.spinup_s, "steps": spin_steps},
         "ms_per_step_repeats": {"median": repeats[2], "min": repeats[0], "max": repeats[4]},
         "kernels": kernels,
         "roofline": roofline,
