@@ -119,7 +119,7 @@ hipError_t launch_context(const AttnShape &s, const float *P, const void *V, con
 // A lane loads four consecutive d of its row for both operands and spends
 // them on four MFMA steps, so the k index of step c is d0 + 4*(l/16) + c on
 // both sides.
-template <typename TV>
+template <typename TV, int G>
 __device__ __forceinline__ void dscore_block(const float *__restrict__ dC, const TV *__restrict__ V,
                                              const float *__restrict__ P, const int *__restrict__ key_len,
                                              float *__restrict__ dS, float *__restrict__ ds_rowsum,
@@ -132,27 +132,37 @@ __device__ __forceinline__ void dscore_block(const float *__restrict__ dC, const
     const float *dCb = dC + (size_t)b * Tq * Dv;
     const TV *Vb = V + (size_t)b * Tk * Dv;
 
-    // Wave w takes key tiles w, w+4, ..., four at a time so that one fragment of dC feeds four products (the
-    // kernel is bound by what the L1 can deliver, not by the matrix cores).  The sum over d runs in stages of U
+    // Wave w takes key tiles w, w+4, ..., G at a time so that one fragment of dC feeds G products (the
+    // kernel is bound by what the L1 can deliver, not by the matrix cores); tiles past the sample's last one are
+    // neither loaded nor multiplied.  The sum over d runs in stages of U
     // 16-wide slices; the loads of the next stage are in flight while the current one is multiplied.  Rows and
     // keys past the end are clamped for loading; what they produce is never read.  Columns past Dv are zeroed.
     const int n_jt = (L + 15) / 16;
-    constexpr int U = 2, G = 4;
+    constexpr int U = 2;
     const int n_st = (Dv + 16 * U - 1) / (16 * U);            // stages
     const bool ragged = Dv % (16 * U) != 0;
     const float *dCrow = dCb + (size_t)min(i0 + lm, Tq - 1) * Dv;
-    for (int jt0 = w; jt0 < n_jt; jt0 += 4 * G) {              // this wave's tiles jt0, jt0 + 4, jt0 + 8, jt0 + 12
+    for (int jt0 = w; jt0 < n_jt; jt0 += 4 * G) {              // this wave's tiles jt0, jt0 + 4, jt0 + 8, ...
         const TV *vrow[G];
 #pragma unroll
         for (int k = 0; k < G; ++k) vrow[k] = Vb + (size_t)min((jt0 + 4 * k) * 16 + lm, Tk - 1) * Dv;
         float4 a[U], bv[G][U], an[U], bn[G][U];
+#pragma unroll
+        for (int k = 0; k < G; ++k)
+#pragma unroll
+            for (int u = 0; u < U; ++u) bv[k][u] = bn[k][u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        // key tiles of this group that exist (the same in all lanes): the others are neither loaded nor multiplied
+        bool live[G];
+#pragma unroll
+        for (int k = 0; k < G; ++k) live[k] = jt0 + 4 * k < n_jt;
         auto load = [&](float4 (&da)[U], float4 (&db)[G][U], int st) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int d = min((st * U + u) * 16 + 4 * lk, Dv - 4);
                 da[u] = ld4(dCrow, (size_t)d);
 #pragma unroll
-                for (int k = 0; k < G; ++k) db[k][u] = ld4(vrow[k], (size_t)d);
+                for (int k = 0; k < G; ++k)
+                    if (live[k]) db[k][u] = ld4(vrow[k], (size_t)d);
             }
         };
         load(a, bv, 0);
@@ -169,13 +179,13 @@ __device__ __forceinline__ void dscore_block(const float *__restrict__ dC, const
 #pragma unroll
             for (int u = 0; u < U; ++u) {
 #pragma unroll
-                for (int k = 0; k < G; ++k) acc[k] = mfma16(a[u].x, bv[k][u].x, acc[k]);
+                for (int k = 0; k < G; ++k) if (live[k]) acc[k] = mfma16(a[u].x, bv[k][u].x, acc[k]);
 #pragma unroll
-                for (int k = 0; k < G; ++k) acc[k] = mfma16(a[u].y, bv[k][u].y, acc[k]);
+                for (int k = 0; k < G; ++k) if (live[k]) acc[k] = mfma16(a[u].y, bv[k][u].y, acc[k]);
 #pragma unroll
-                for (int k = 0; k < G; ++k) acc[k] = mfma16(a[u].z, bv[k][u].z, acc[k]);
+                for (int k = 0; k < G; ++k) if (live[k]) acc[k] = mfma16(a[u].z, bv[k][u].z, acc[k]);
 #pragma unroll
-                for (int k = 0; k < G; ++k) acc[k] = mfma16(a[u].w, bv[k][u].w, acc[k]);
+                for (int k = 0; k < G; ++k) if (live[k]) acc[k] = mfma16(a[u].w, bv[k][u].w, acc[k]);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -483,7 +493,11 @@ __global__ __launch_bounds__(256, 3) void k_bwd_pre(const float *__restrict__ dC
         if (Tk <= kDsplitMaxTk)
             dscore_block_dsplit<TV>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
         else
-            dscore_block<TV>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
+            // a wave's key tiles in groups of four, or of five where that takes all of them at once (17 to 20 key tiles)
+            if ((Tk + 15) / 16 > 16 && (Tk + 15) / 16 <= 20)
+                dscore_block<TV, 5>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
+            else
+                dscore_block<TV, 4>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
         return;
     }
     li -= spx * s_tiles;
