@@ -83,6 +83,18 @@ EDGE = [
     ("row_mode_four_slices", 2, 10, 32, 1024, 16, "f32", [32, 5]),
     ("row_mode_bf16_four_slices", 2, 9, 30, 900, 16, "bf16", None),
     ("streaming_mode_just_past_row_mode", 2, 11, 65, 512, 16, "f32", [65, 64]),
+    # streaming mode runs blocks of four waves up to H = 512 and of eight beyond
+    ("forward_four_wave_blocks", 3, 19, 100, 512, 64, "f32", [100, 61, 3]),
+    ("forward_four_wave_blocks_ragged_h", 2, 9, 70, 300, 12, "f32", None),
+    ("forward_eight_wave_streaming_past_512", 2, 9, 70, 516, 12, "f32", None),
+    # dV: a block owns all keys up to four key tiles (Tk <= 64), one key tile beyond; value width not a multiple of 64
+    ("dv_all_keys_form_four_tiles", 2, 21, 64, 64, 72, "f32", [64, 17]),
+    ("dv_per_tile_form_just_past", 2, 21, 65, 64, 72, "f32", [65, 16]),
+    # dS on long key axes: a wave's key tiles in groups of four (16 and 21 tiles) or five (19 tiles), tiles past a
+    # sample's last one skipped
+    ("ds_sixteen_key_tiles", 1, 17, 256, 64, 8, "f32", [250]),
+    ("ds_groups_of_five_key_tiles", 3, 20, 300, 64, 24, "f32", [300, 260, 40]),
+    ("ds_groups_of_four_past_twenty_tiles", 2, 10, 330, 64, 8, "f32", [330, 130]),
 ]
 
 
@@ -106,6 +118,8 @@ GUARDED = [
     ("guard_unfused_forward", 2, 19, 23, 70, 12, "f32", False),
     ("guard_bf16", 3, 21, 34, 130, 20, "bf16", False),
     ("guard_long_keys", 1, 9, 300, 64, 8, "f32", False),
+    ("guard_dv_all_keys_form", 2, 21, 64, 64, 72, "f32", False),
+    ("guard_four_wave_forward", 2, 9, 70, 300, 12, "f32", False),
     ("guard_stash", 4, 6, 7, 16, 16, "f32", True),
 ]
 
