@@ -3,9 +3,10 @@
 // (Section 2, attention steps 1-2; Section 4.1 scoring function; Section 6.1:
 // one fused kernel instead of many small ones, fewer launches and accesses).
 //
-// Block = (sample b, up to RT = 8 NG query rows), 8 waves.
+// Block = (sample b, up to RT = 8 NG query rows), W waves: eight, or four in streaming mode at H <= 512 (four
+// such blocks share a CU and are in different phases of their lives, which keeps the vector units fed).
 //   A  exp(2q) / v of the rows and 1 / v go to LDS (taken once per block).
-//   B  the valid keys are dealt to the waves in eight contiguous shares that differ by at most one key;
+//   B  the valid keys are dealt to the waves in W contiguous shares that differ by at most one key;
 //      a wave walks its share in passes of up to four keys.  A lane owns four
 //      consecutive h of every 256-wide slice, so a key row arrives as one
 //      16-byte load per lane (every K element is exponentiated once per block)
