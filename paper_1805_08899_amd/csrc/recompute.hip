@@ -336,7 +336,10 @@ static hipError_t launch_recompute_t(const AttnShape &s, const void *Qp, const v
                                      unsigned long long epoch, float *dv, hipStream_t st) {
     const int max_rows = RC_W * RC_RI;
     const int n_pass = (s.Tq + max_rows - 1) / max_rows;
-    const int rows_per_pass = (s.Tq + n_pass - 1) / n_pass;
+    // full passes of 64 rows first, the remainder last: with the rows split evenly over the passes, waves of 7 and of 8
+    // rows meet at every tile's barrier (100 rows: 64 + 36 instead of 50 + 50; backward 141.5 -> 139.8 us at B = 128)
+    const int rows_per_pass = s.Tq > max_rows ? max_rows : s.Tq;
+    (void)n_pass;
     dim3 grid((s.H + 63) / 64, s.B);
     if (tmap)
         k_recompute<T, true><<<grid, RC_THREADS, 0, st>>>((const T *)Qp, (const T *)Kp, (const T *)v, order, dS,
