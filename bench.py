@@ -307,20 +307,30 @@ def calibrate(eb, torch, dev):
         "fwd_mix_tanh_per_s": run(eb.ECHO_CAL_FWD_MIX),
         "bwd_mix_tanh_per_s": run(eb.ECHO_CAL_BWD_MIX),
     }
-    n = 1 << 28   # 256 MiB each way
-    src = torch.empty(n, dtype=torch.uint8, device=dev)
-    dst = torch.empty(n, dtype=torch.uint8, device=dev)
-    out["copy_read_plus_write_bytes_per_s"] = 2 * run(eb.ECHO_CAL_COPY, src=src, dst=dst, nbytes=n)
-    del src, dst
-    # The 256 MiB copy above runs out of the 256 MB on-die cache behind the L2s and reads more than the 8 TB/s of
-    # the HBM; a copy of 1 GiB each way does not fit there and shows what the memory itself delivers to a plain
-    # two-stream copy (about 5 TB/s).  The dropout codec at 2^26 elements moves the same bytes as the 256 MiB copy and
-    # is compared with it; the LSTM block at 16384 x 1024 moves 0.8 to 1 GB per launch and is compared with the 1 GiB
-    # copy; both also against the published peak.
-    n = 1 << 30
-    src = torch.empty(n, dtype=torch.uint8, device=dev)
-    dst = torch.empty(n, dtype=torch.uint8, device=dev)
-    out["copy_beyond_cache_read_plus_write_bytes_per_s"] = 2 * run(eb.ECHO_CAL_COPY, src=src, dst=dst, nbytes=n)
+    def copy_rate(n, reps):
+        """Bytes read plus written per second by a plain copy of n bytes: one thread per 16 bytes (the launch
+        shape of the streaming kernels; a fixed grid striding over the buffers is slower), launched back to back
+        like every other row of this file and averaged."""
+        src = torch.empty(n, dtype=torch.uint8, device=dev)
+        dst = torch.empty(n, dtype=torch.uint8, device=dev)
+        go = lambda: eb.check(eb.echo_attn_calibrate(eb.ECHO_CAL_COPY, n // 16 // 256, 1, src, dst, n, stream=st)[0],
+                              "echo_attn_calibrate")
+        for _ in range(3):
+            go()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize(dev)
+        a.record()
+        for _ in range(reps):
+            go()
+        b.record()
+        torch.cuda.synchronize(dev)
+        return 2 * n / (a.elapsed_time(b) * 1e-3 / reps)
+
+    # 256 MiB each way: the bytes of one pass of the dropout codec over 2^26 elements; the 256 MB on-die cache
+    # behind the L2s still helps here.  1 GiB each way does not fit there and shows what the memory itself gives a
+    # two-stream copy; the LSTM block at 16384 x 1024 (0.8 to 1 GB per launch) is compared with that one.
+    out["copy_read_plus_write_bytes_per_s"] = copy_rate(1 << 28, 20)
+    out["copy_beyond_cache_read_plus_write_bytes_per_s"] = copy_rate(1 << 30, 8)
     return out
 
 

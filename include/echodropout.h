@@ -38,7 +38,7 @@ extern "C" {
 size_t echo_dropout_mask_words(size_t n);
 
 /* Forward: y and the one-bit feature map (Section 5.2, encode).
- * Errors: ECHO_ERR_NULL, ECHO_ERR_SHAPE (n == 0 or p outside [0, 1)), ECHO_ERR_ALIGN, ECHO_ERR_HIP. */
+ * Errors: ECHO_ERR_NULL, ECHO_ERR_SHAPE (n == 0, n beyond 2^40 or p outside [0, 1)), ECHO_ERR_ALIGN, ECHO_ERR_HIP. */
 echo_status_t echo_dropout_fwd(const float *x, size_t n, float p, uint64_t seed, uint64_t offset,
                                float *y, uint32_t *mask_bits, void *stream);
 

@@ -26,7 +26,7 @@
  * by the same lane); no other overlap between inputs and outputs is allowed.  dc may be NULL: no gradient
  * reaches c from a later step.  da is the gradient of Gx and of Gh alike.  Outputs are overwritten.  Work is
  * enqueued on `stream` (hipStream_t as void*); no synchronisation, no allocation, no global state.
- * Errors: ECHO_ERR_NULL, ECHO_ERR_SHAPE (B or H < 1, or B * H beyond 2^40), ECHO_ERR_ALIGN, ECHO_ERR_HIP.
+ * Errors: ECHO_ERR_NULL, ECHO_ERR_SHAPE (B or H < 1, or B * H beyond 2^38), ECHO_ERR_ALIGN, ECHO_ERR_HIP.
  */
 #ifndef ECHOLSTM_H
 #define ECHOLSTM_H

@@ -4,6 +4,9 @@
 //
 // A lane owns four consecutive elements (one 16-byte load and store, and exactly one Philox4x32-10 block);
 // eight consecutive lanes own the 32 elements of one mask word and assemble it with three exchanges.
+// The launch has one thread per four elements: blocks start in address order, so the blocks that run at any
+// moment cover a narrow window of the arrays.  A fixed grid of 4096 blocks striding over the arrays measured
+// 14 % slower (forward, 2^26 elements) and 20 % slower once the arrays no longer fit the on-die cache.
 #include "../../include/echodropout.h"
 
 #include <hip/hip_runtime.h>
@@ -40,8 +43,8 @@ __global__ __launch_bounds__(256) void k_dropout_fwd(const float *__restrict__ x
                                                     uint32_t off_hi, float *__restrict__ y,
                                                     uint32_t *__restrict__ mask_bits, size_t n_quads) {
     const int lane = lane_id();
-    for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < (n_quads + 7) / 8 * 8;   // whole words per wave pass
-         q += (size_t)gridDim.x * 256) {
+    const size_t q = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (q < (n_quads + 7) / 8 * 8) {          // whole mask words: the eight lanes of a group stay together
         const size_t i = 4 * q;
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
         if (i + 3 < n) v = *reinterpret_cast<const float4 *>(x + i);
@@ -73,24 +76,31 @@ __global__ __launch_bounds__(256) void k_dropout_fwd(const float *__restrict__ x
 __global__ __launch_bounds__(256) void k_dropout_bwd(const float *__restrict__ dy,
                                                     const uint32_t *__restrict__ mask_bits, size_t n, float scale,
                                                     float *__restrict__ dx, size_t n_quads) {
-    for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < n_quads; q += (size_t)gridDim.x * 256) {
+    const size_t q = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (q < n_quads) {
         const size_t i = 4 * q;
-        const uint32_t bits = mask_bits[q / 8] >> (4 * (q & 7));        // the eight lanes of a group share the word
-        if (i + 3 < n) {
-            const float4 v = *reinterpret_cast<const float4 *>(dy + i);
-            store4_streaming(dx + i, make_float4((bits & 1u) ? v.x * scale : 0.f, (bits & 2u) ? v.y * scale : 0.f,
-                                                 (bits & 4u) ? v.z * scale : 0.f, (bits & 8u) ? v.w * scale : 0.f));
-        } else {
-            for (int c = 0; c < 3 && i + c < n; ++c) dx[i + c] = ((bits >> c) & 1u) ? dy[i + c] * scale : 0.f;
+        // both loads leave before either is awaited (the eight lanes of a group share the mask word)
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (i + 3 < n) v = *reinterpret_cast<const float4 *>(dy + i);
+        else {
+            v.x = dy[i];
+            if (i + 1 < n) v.y = dy[i + 1];
+            if (i + 2 < n) v.z = dy[i + 2];
+        }
+        const uint32_t bits = mask_bits[q / 8] >> (4 * (q & 7));
+        const float4 o = make_float4((bits & 1u) ? v.x * scale : 0.f, (bits & 2u) ? v.y * scale : 0.f,
+                                     (bits & 4u) ? v.z * scale : 0.f, (bits & 8u) ? v.w * scale : 0.f);
+        if (i + 3 < n) store4_streaming(dx + i, o);
+        else {
+            dx[i] = o.x;
+            if (i + 1 < n) dx[i + 1] = o.y;
+            if (i + 2 < n) dx[i + 2] = o.z;
         }
     }
 }
 
-static int stream_grid(size_t n_quads) {
-    const size_t blocks = (n_quads + 255) / 256;
-    const size_t cap = 256 * 16;            // 16 blocks per CU: enough to saturate HBM, grid-stride beyond that
-    return (int)(blocks < cap ? (blocks ? blocks : 1) : cap);
-}
+constexpr size_t kMaxElements = (size_t)1 << 40;      // 2^30 blocks of 256 quads
+static unsigned stream_grid(size_t n_quads) { return (unsigned)((n_quads + 255) / 256); }
 
 }  // namespace echo
 
@@ -101,7 +111,7 @@ size_t echo_dropout_mask_words(size_t n) { return (n + 31) / 32; }
 echo_status_t echo_dropout_fwd(const float *x, size_t n, float p, uint64_t seed, uint64_t offset, float *y,
                                uint32_t *mask_bits, void *stream) {
     if (!x || !y || !mask_bits) return ECHO_ERR_NULL;
-    if (n == 0 || !(p >= 0.f) || !(p < 1.f)) return ECHO_ERR_SHAPE;
+    if (n == 0 || n > echo::kMaxElements || !(p >= 0.f) || !(p < 1.f)) return ECHO_ERR_SHAPE;
     if (((uintptr_t)x | (uintptr_t)y | (uintptr_t)mask_bits) & 15u) return ECHO_ERR_ALIGN;
     const size_t n_quads = (n + 3) / 4;
     const float scale = 1.0f / (1.0f - p);
@@ -114,7 +124,7 @@ echo_status_t echo_dropout_fwd(const float *x, size_t n, float p, uint64_t seed,
 echo_status_t echo_dropout_bwd(const float *dy, const uint32_t *mask_bits, size_t n, float p, float *dx,
                                void *stream) {
     if (!dy || !dx || !mask_bits) return ECHO_ERR_NULL;
-    if (n == 0 || !(p >= 0.f) || !(p < 1.f)) return ECHO_ERR_SHAPE;
+    if (n == 0 || n > echo::kMaxElements || !(p >= 0.f) || !(p < 1.f)) return ECHO_ERR_SHAPE;
     if (((uintptr_t)dy | (uintptr_t)dx | (uintptr_t)mask_bits) & 15u) return ECHO_ERR_ALIGN;
     const size_t n_quads = (n + 3) / 4;
     const float scale = 1.0f / (1.0f - p);

@@ -149,6 +149,8 @@ def test_dropout_rejects_bad_arguments_without_launching():
     assert eb.echo_dropout_mask_words(33) == 2
     assert eb.echo_dropout_fwd(None, 8, 0.5, 1, 0, A, A) == eb.ECHO_ERR_NULL
     assert eb.echo_dropout_fwd(A, 0, 0.5, 1, 0, A, A) == eb.ECHO_ERR_SHAPE
+    assert eb.echo_dropout_fwd(A, (1 << 40) + 1, 0.5, 1, 0, A, A) == eb.ECHO_ERR_SHAPE   # one thread per four elements
+    assert eb.echo_dropout_bwd(A, A, (1 << 40) + 1, 0.5, A) == eb.ECHO_ERR_SHAPE
     assert eb.echo_dropout_fwd(A, 8, 1.0, 1, 0, A, A) == eb.ECHO_ERR_SHAPE
     assert eb.echo_dropout_fwd(A, 8, -0.1, 1, 0, A, A) == eb.ECHO_ERR_SHAPE
     assert eb.echo_dropout_fwd(A + 4, 8, 0.5, 1, 0, A, A) == eb.ECHO_ERR_ALIGN
@@ -164,6 +166,8 @@ def test_lstm_cell_rejects_bad_arguments_without_launching():
     assert eb.echo_lstm_cell_fwd(0, 8, A, A, A, A, A, A) == eb.ECHO_ERR_SHAPE
     assert eb.echo_lstm_cell_fwd(4, -1, A, A, A, A, A, A) == eb.ECHO_ERR_SHAPE
     assert eb.echo_lstm_cell_fwd(1 << 30, 1 << 30, A, A, A, A, A, A) == eb.ECHO_ERR_SHAPE
+    assert eb.echo_lstm_cell_fwd(1 << 20, (1 << 18) + 1, A, A, A, A, A, A) == eb.ECHO_ERR_SHAPE   # B H beyond 2^38
+    assert eb.echo_lstm_cell_bwd(1 << 20, (1 << 18) + 1, A, A, A, A, A, A) == eb.ECHO_ERR_SHAPE
     assert eb.echo_lstm_cell_fwd(4, 8, A, A, A + 4, A, A, A) == eb.ECHO_ERR_ALIGN
     assert eb.echo_lstm_cell_bwd(4, 8, None, A, A, A, A, A) == eb.ECHO_ERR_NULL
     assert eb.echo_lstm_cell_bwd(4, 8, A, A + 8, A, A, A, A) == eb.ECHO_ERR_ALIGN
