@@ -195,9 +195,11 @@ __device__ __forceinline__ int clamp_len(int len, int Tk) { return len < 0 ? 0 :
 // 0, 5, 2, 7, 4, 1, 6, 3 in that order: the SIMDs' totals then differ by at most one item, where the plain
 // floor(n w / 8) split would hand both longer ranges of n % 8 == 2 to one SIMD.
 __device__ __forceinline__ int deal8_begin(int n, int w) {
-    // kLonger[e]: bit w set if wave w gets a longer range when n % 8 == e
-    constexpr unsigned kLonger[8] = {0x00u, 0x01u, 0x21u, 0x25u, 0xa5u, 0xb5u, 0xb7u, 0xf7u};
-    const unsigned m = kLonger[n & 7];
+    // byte e: bit w set if wave w gets a longer range when n % 8 == e (0x00, 0x01, 0x21, 0x25, 0xa5, 0xb5, 0xb7,
+    // 0xf7).  Packed into one immediate: as an array the table sits in memory, and the scalar load that fetches
+    // it is a trip to memory at the start of a block, right in front of the loads that depend on the ranges.
+    constexpr unsigned long long kLonger = 0xf7b7b5a525210100ull;
+    const unsigned m = (unsigned)(kLonger >> (8 * (n & 7))) & 0xffu;
     return (n >> 3) * w + __builtin_popcount(m & ((1u << w) - 1u));
 }
 

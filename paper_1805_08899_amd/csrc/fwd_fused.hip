@@ -61,6 +61,31 @@ constexpr int fw_row_max_keys(int ns) { return ns <= 0 ? 1 : (FW_ROW_REGS / ns >
 
 __device__ __forceinline__ float comp(const float4 &x, int c) { return c == 0 ? x.x : c == 1 ? x.y : c == 2 ? x.z : x.w; }
 
+// Four consecutive elements of a key row exactly as they were loaded: one 16- or 8-byte register group that stays
+// whole from the load to pin().  Row mode loads its keys under uniform branches (a wave requests only its own
+// keys); if the loaded value were taken apart or converted right away, the compiler would merge those pieces with
+// the other branch's zeros inside the branch and wait for every key in turn behind its load: one trip to memory per
+// key instead of one for all.  pin() marks the place from where the value may be used.
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+template <typename T> struct RawKey;
+template <> struct RawKey<float> {
+    f32x4 v;
+    __device__ __forceinline__ void load(const float *p, size_t i) { v = *reinterpret_cast<const f32x4 *>(p + i); }
+    __device__ __forceinline__ void zero() { v = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    __device__ __forceinline__ void pin() { asm("" : "+v"(v)); }
+    __device__ __forceinline__ float4 get() const { return make_float4(v.x, v.y, v.z, v.w); }
+};
+template <> struct RawKey<bf16_t> {
+    u32x2 v;
+    __device__ __forceinline__ void load(const bf16_t *p, size_t i) { v = *reinterpret_cast<const u32x2 *>(p + i); }
+    __device__ __forceinline__ void zero() { v = u32x2{0u, 0u}; }
+    __device__ __forceinline__ void pin() { asm("" : "+v"(v)); }
+    __device__ __forceinline__ float4 get() const {
+        return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u),
+                           __uint_as_float(v.y << 16), __uint_as_float(v.y & 0xffff0000u));
+    }
+};
+
 // Pairs of reciprocals share one division (see B at the top): the product a0 a1 must stay finite.
 // |a| <= max|1/v| + max|exp(2q)/v| max exp(2k); a pass is evaluated by the factor path only while this
 // bound is below kPairLimit = sqrt(FLT_MAX) (with a little room).  An entry of v below kTinyV in magnitude
@@ -246,12 +271,12 @@ __device__ __noinline__ void fw_pass_exact(const T *__restrict__ qrow0, int ni, 
 }
 
 // Row mode, for key shares small enough to sit in registers: NK keys x NS slices of exp(2k) per lane, loaded
-// once (raw: the values as loaded before the staging barrier); then a plain loop over the tile's rows, each
-// row against all NK keys, ending in one transposing reduction of the row's NK sums.  The loop body is short
+// once (raw: the values as loaded before the staging barrier; this call takes keys C0 .. C0 + NK - 1 of them); then
+// a plain loop over the tile's rows, each row against all NK keys, ending in one transposing reduction of the row's NK sums.  The loop body is short
 // and runs ni times, where streaming mode spends most of a short block's life in code it runs once.
 // Returns true (nothing written) if the operands may leave the range of the factor path.
-template <int NS, int NKM, int NK>
-__device__ __forceinline__ bool fw_rows(const float4 (&raw)[NS][NKM], const float *__restrict__ s_e,
+template <typename T, int NS, int NKM, int NK, int C0 = 0>
+__device__ __forceinline__ bool fw_rows(const RawKey<T> (&raw)[NS][NKM], const float *__restrict__ s_e,
                                         const float *__restrict__ s_c, int Hp, int ni, float qe_max, float c_max,
                                         float *__restrict__ s_S, int spitch, int jcol0) {
     const int lane = lane_id();
@@ -261,8 +286,9 @@ __device__ __forceinline__ bool fw_rows(const float4 (&raw)[NS][NKM], const floa
     for (int s = 0; s < NS; ++s)
 #pragma unroll
         for (int c = 0; c < NK; ++c) {
+            const float4 kx = raw[s][C0 + c].get();
 #pragma unroll
-            for (int q = 0; q < 4; ++q) fk[s][q][c] = fast_exp2(kTwoLog2e * comp(raw[s][c], q));
+            for (int q = 0; q < 4; ++q) fk[s][q][c] = fast_exp2(kTwoLog2e * comp(kx, q));
             kmax = fmaxf(fmaxf(kmax, fk[s][0][c]), fmaxf(fk[s][1][c], fmaxf(fk[s][2][c], fk[s][3][c])));
         }
     if (__any(!(__builtin_fmaf(qe_max, kmax, c_max) < kPairLimit))) return true;
@@ -321,13 +347,23 @@ __device__ __forceinline__ bool fw_rows(const float4 (&raw)[NS][NKM], const floa
     return false;
 }
 
-template <int NS, int NKM>
-__device__ __forceinline__ bool fw_rows_n(int nk, const float4 (&raw)[NS][NKM], const float *__restrict__ s_e,
+template <typename T, int NS, int NKM>
+__device__ __forceinline__ bool fw_rows_n(int nk, const RawKey<T> (&raw)[NS][NKM], const float *__restrict__ s_e,
                                           const float *__restrict__ s_c, int Hp, int ni, float qe_max, float c_max,
                                           float *__restrict__ s_S, int spitch, int jcol0) {
-#define FW_ROWS_CASE(N)                                                                                  \
-    case N:                                                                                              \
-        if constexpr (N <= NKM) return fw_rows<NS, NKM, N>(raw, s_e, s_c, Hp, ni, qe_max, c_max, s_S, spitch, jcol0); \
+    // More than twelve 16-byte groups of exponentials (keys x slices) do not fit the registers next to the row
+    // loop's operands: the loop would fetch them back from scratch memory row after row.  Such a share is
+    // evaluated as two halves, each with its own loop over the rows.
+#define FW_ROWS_CASE(N)                                                                                       \
+    case N:                                                                                                   \
+        if constexpr (N <= NKM && NS * N <= 12) {                                                             \
+            return fw_rows<T, NS, NKM, N>(raw, s_e, s_c, Hp, ni, qe_max, c_max, s_S, spitch, jcol0);          \
+        } else if constexpr (N <= NKM) {                                                                      \
+            constexpr int A = (N + 1) / 2;                                                                    \
+            const bool r1 = fw_rows<T, NS, NKM, A, 0>(raw, s_e, s_c, Hp, ni, qe_max, c_max, s_S, spitch, jcol0);         \
+            const bool r2 = fw_rows<T, NS, NKM, N - A, A>(raw, s_e, s_c, Hp, ni, qe_max, c_max, s_S, spitch, jcol0 + A); \
+            return r1 || r2;                                                                                  \
+        }                                                                                                     \
         break;
     switch (nk) {
         FW_ROWS_CASE(1) FW_ROWS_CASE(2) FW_ROWS_CASE(3) FW_ROWS_CASE(4)
@@ -599,7 +635,7 @@ __global__ __launch_bounds__(64 * W, NG == 1 ? 4 : 2) void k_fwd_fused(
     const int k_lo = deal_begin<W>(L, w);
     const int nk = deal_begin<W>(L, w + 1) - k_lo;
     KeyStream<T> ks;
-    float4 raw[ROWMODE ? ROWNS : 1][NKM];
+    RawKey<T> raw[ROWMODE ? ROWNS : 1][NKM];
     if constexpr (ROWMODE) {
         // only the wave's own keys are requested (every load takes its turn in the CU's address unit whether
         // it hits or not); the branches are uniform and everything is awaited at the staging barrier anyway
@@ -609,11 +645,11 @@ __global__ __launch_bounds__(64 * W, NG == 1 ? 4 : 2) void k_fwd_fused(
 #pragma unroll
                 for (int s = 0; s < ROWNS; ++s) {
                     const int hc = min(s * FW_SS + 4 * lane, H - 4);   // columns past H: see KeyStream::fetch
-                    raw[s][c] = ld4(kb, (size_t)(unsigned)((k_lo + c) * H + hc));
+                    raw[s][c].load(kb, (size_t)(unsigned)((k_lo + c) * H + hc));
                 }
             } else {
 #pragma unroll
-                for (int s = 0; s < ROWNS; ++s) raw[s][c] = make_float4(0.f, 0.f, 0.f, 0.f);
+                for (int s = 0; s < ROWNS; ++s) raw[s][c].zero();
             }
         }
     } else {
@@ -673,7 +709,12 @@ __global__ __launch_bounds__(64 * W, NG == 1 ? 4 : 2) void k_fwd_fused(
     // ---- B: scores of this wave's keys
     __builtin_amdgcn_s_setprio(0);
     if constexpr (ROWMODE) {
-        if (fw_rows_n<ROWNS, NKM>(nk, raw, s_e, s_c, Hp, ni, qe_max, c_max, s_S, spitch, k_lo))
+        // the keys are used from here on (see RawKey)
+#pragma unroll
+        for (int s = 0; s < ROWNS; ++s)
+#pragma unroll
+            for (int c = 0; c < NKM; ++c) raw[s][c].pin();
+        if (fw_rows_n<T, ROWNS, NKM>(nk, raw, s_e, s_c, Hp, ni, qe_max, c_max, s_S, spitch, k_lo))
             fw_pass_exact<T>(qb, ni, kb + (size_t)k_lo * H, nk, H, v, s_S, spitch, k_lo);
     } else {
         for (int p = 0; p < ks.npass; ++p) {                   // passes of up to FW_NJ keys
