@@ -16,7 +16,8 @@ CASES = [
     (33, 0.1, 3, 1 << 40),
     (4 * 256 * 7 + 3, 0.5, (1 << 63) + 12345, 7),          # several blocks and a ragged tail
     (1 << 20, 0.2, 42, 0),
-    (50 * 128 * 1024 + 17, 0.1, 7, 99),                      # grid-stride loop (more quads than one pass), ragged
+    (50 * 128 * 1024 + 17, 0.1, 7, 99),                      # 6400 blocks of 256 quads and a ragged tail
+    ((1 << 24) + 4 * 256 * 3 + 2, 0.25, 11, 1 << 33),        # more than 65535 blocks, ragged
     (1000, 0.0, 9, 9),                                       # keep everything
 ]
 

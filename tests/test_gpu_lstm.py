@@ -22,7 +22,7 @@ CASES = [
     (128, 512, 1.0),             # the translation model's cell
     (128, 1024, 1.5),
     (7, 4 * 67, 3.0),            # ragged block tail, many saturated gates
-    (4100, 1024, 1.0),           # more items than one pass of the grid: the grid-stride loop
+    (4100, 1024, 1.0),           # 4100 blocks of 256 items
     (33, 1023, 1.0),             # long odd rows
 ]
 
