@@ -203,26 +203,52 @@ __device__ __forceinline__ void dscore_block(const float *__restrict__ dC, const
             }
         }
     }
+    // P of the four rows this wave finishes, the first NP keys per lane of each: requested together before the
+    // barrier (the registers of the product loop are free by now), where loading row after row inside the loop
+    // below put one trip to memory behind the other
+    constexpr int NP = 5;
+    float pr[4][NP];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const float *p = P + ((size_t)b * Tq + min(i0 + w + 4 * t, Tq - 1)) * Tk;
+#pragma unroll
+        for (int c = 0; c < NP; ++c) pr[t][c] = p[min(lane + 64 * c, Tk - 1)];
+    }
     lds_barrier();
 
-    for (int rr = w; rr < 16; rr += 4) {
-        const int i = i0 + rr;
-        if (i >= Tq) break;
-        const float *p = P + ((size_t)b * Tq + i) * Tk;
-        const float *dp = s_dp + rr * pitch16;
-        float *ds = dS + ((size_t)b * Tq + i) * pitch;
-        float r = 0.f;
-        for (int j = lane; j < L; j += 64) r += p[j] * dp[j];
-        r = wave_sum(r);
-        float tot = 0.f;
-        for (int j = lane; j < pitch; j += 64) {
-            float x = 0.f;
-            if (j < L) x = p[j] * (dp[j] - r);
-            ds[j] = x;
-            tot += x;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int rr = w + 4 * t, i = i0 + rr;
+        if (i < Tq) {
+            const float *p = P + ((size_t)b * Tq + i) * Tk;
+            const float *dp = s_dp + rr * pitch16;
+            float *ds = dS + ((size_t)b * Tq + i) * pitch;
+            float r = 0.f;
+#pragma unroll
+            for (int c = 0; c < NP; ++c)
+                if (lane + 64 * c < L) r += pr[t][c] * dp[lane + 64 * c];
+            for (int j = lane + 64 * NP; j < L; j += 64) r += p[j] * dp[j];
+            r = wave_sum(r);
+            float tot = 0.f;
+#pragma unroll
+            for (int c = 0; c < NP; ++c) {
+                const int j = lane + 64 * c;
+                if (j < pitch) {
+                    float x = 0.f;
+                    if (j < L) x = pr[t][c] * (dp[j] - r);
+                    ds[j] = x;
+                    tot += x;
+                }
+            }
+            for (int j = lane + 64 * NP; j < pitch; j += 64) {
+                float x = 0.f;
+                if (j < L) x = p[j] * (dp[j] - r);
+                ds[j] = x;
+                tot += x;
+            }
+            tot = wave_sum(tot);
+            if (lane == 0) ds_rowsum[(size_t)b * Tq + i] = tot;
         }
-        tot = wave_sum(tot);
-        if (lane == 0) ds_rowsum[(size_t)b * Tq + i] = tot;
     }
 }
 
@@ -234,6 +260,59 @@ __device__ __forceinline__ void dscore_block(const float *__restrict__ dC, const
 // are added in wave order by the finishing phase, whose P rows were requested at the very start.
 // Rows and keys past the end are clamped for loading; what they produce is never read.
 constexpr int kDsplitMaxTk = 128;
+
+// The finishing phase of a dS block for short key axes: the four waves' planes of partial dP are added in wave order,
+// then dS = P (dP - sum_j P dP) for rows w, w+4, w+8, w+12 of the tile (pr: their P, two keys per lane).
+__device__ __forceinline__ void dsplit_finish(const float (&pr)[4][2], const float *__restrict__ s_dp,
+                                              float *__restrict__ dS, float *__restrict__ ds_rowsum, int b, int i0,
+                                              int Tq, int L, int pitch, int pitch16, int plane) {
+    const int lane = lane_id(), w = wave_id();
+
+    // the four rows together: r = sum_j P dP and sum_j dS by transposing reductions (sum of row t ends up in
+    // lanes 16 t .. 16 t + 15), so the exchanges of the rows overlap instead of queueing behind each other
+    float dp[4][2], rsum[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int rr = w + 4 * t;
+        rsum[t] = 0.f;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int j = lane + 64 * u;
+            const float *q = s_dp + rr * pitch16 + min(j, pitch16 - 1);
+            const float x = ((q[0] + q[plane]) + q[2 * plane]) + q[3 * plane];
+            dp[t][u] = j < L ? x : 0.f;
+            rsum[t] = __builtin_fmaf(j < L ? pr[t][u] : 0.f, dp[t][u], rsum[t]);
+        }
+    }
+    const float r4 = wave_transpose_sum<4>(rsum);
+    float tsum[4], dsv[4][2];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const float r = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(r4), 16 * t));
+        tsum[t] = 0.f;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int j = lane + 64 * u;
+            dsv[t][u] = j < L ? pr[t][u] * (dp[t][u] - r) : 0.f;
+            tsum[t] += dsv[t][u];
+        }
+    }
+    const float t4 = wave_transpose_sum<4>(tsum);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int i = i0 + w + 4 * t;
+        if (i < Tq) {
+            float *ds = dS + ((size_t)b * Tq + i) * pitch;
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+                if (lane + 64 * u < pitch) store_streaming(&ds[lane + 64 * u], dsv[t][u]);
+            if (lane == 16 * t) ds_rowsum[(size_t)b * Tq + i] = t4;
+        }
+    }
+}
+
+// The general form (any width of the value rows): two register groups of a whole round of V slices each, one in
+// flight; with more than one round the dC slices are fetched per key tile and round.
 template <typename TV>
 __device__ __forceinline__ void dscore_block_dsplit(const float *__restrict__ dC, const TV *__restrict__ V,
                                                     const float *__restrict__ P, const int *__restrict__ key_len,
@@ -299,48 +378,90 @@ __device__ __forceinline__ void dscore_block_dsplit(const float *__restrict__ dC
         for (int u = 0; u < U; ++u) bcur[u] = bnxt[u];
     }
     lds_barrier();
+    dsplit_finish(pr, s_dp, dS, ds_rowsum, b, i0, Tq, L, pitch, pitch16, plane);
+}
 
-    // the four rows together: r = sum_j P dP and sum_j dS by transposing reductions (sum of row t ends up in
-    // lanes 16 t .. 16 t + 15), so the exchanges of the rows overlap instead of queueing behind each other
-    float dp[4][2], rsum[4];
+// Value rows of 513 to 1024 columns (two rounds): the wave's slices of the 16 dC rows for both rounds stay in
+// registers for the whole block (the general form above fetches them again for every key tile and round and waits
+// for them each time), and the V slices arrive as a stream of steps (key tile, round, half): four 16-byte loads per
+// lane each, held in four register groups used in turn, so that three steps are under way while one is multiplied.
+// Past the last step the stream repeats it.  Measured at B = 128, T = 50, Dv = 1024: backward 92.0 -> 87.6 us.  (For
+// one round, where dC is kept already, the finer stream measured 1 % slower than two groups of a whole round.)
+template <typename TV>
+__device__ __forceinline__ void dscore_block_dsplit2(const float *__restrict__ dC, const TV *__restrict__ V,
+                                                    const float *__restrict__ P, const int *__restrict__ key_len,
+                                                    float *__restrict__ dS, float *__restrict__ ds_rowsum,
+                                                    float *__restrict__ s_dp, int b, int i0, int Tq, int Tk,
+                                                    int Dv, int pitch) {
+    const int lane = lane_id(), w = wave_id();
+    const int lm = lane & 15, lk = lane >> 4;
+    const int pitch16 = (Tk + 15) / 16 * 16 + 4;
+    const int plane = 16 * pitch16;
+    // P of the rows this wave finishes (rows w, w+4, w+8, w+12 of the tile), two keys per lane
+    float pr[4][2];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-        const int rr = w + 4 * t;
-        rsum[t] = 0.f;
+        const int i = min(i0 + w + 4 * t, Tq - 1);
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int j = lane + 64 * u;
-            const float *q = s_dp + rr * pitch16 + min(j, pitch16 - 1);
-            const float x = ((q[0] + q[plane]) + q[2 * plane]) + q[3 * plane];
-            dp[t][u] = j < L ? x : 0.f;
-            rsum[t] = __builtin_fmaf(j < L ? pr[t][u] : 0.f, dp[t][u], rsum[t]);
-        }
+        for (int u = 0; u < 2; ++u) pr[t][u] = P[((size_t)b * Tq + i) * Tk + min(lane + 64 * u, Tk - 1)];
     }
-    const float r4 = wave_transpose_sum<4>(rsum);
-    float tsum[4], dsv[4][2];
+    const float *dCrow = dC + ((size_t)b * Tq + min(i0 + lm, Tq - 1)) * Dv;
+    const TV *Vb = V + (size_t)b * Tk * Dv;
+    constexpr int ROUNDS = 2;
+    constexpr int U = 8;                          // 16-wide slices of d per wave and round
+    constexpr int US = 4;                         // slices per step
+    float4 a[ROUNDS][U], bb[4][US];
+    auto load_b = [&](float4 (&dst)[US], int jt, int r, int half) {
+        const TV *row = Vb + (size_t)min(jt * 16 + lm, Tk - 1) * Dv;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const float r = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(r4), 16 * t));
-        tsum[t] = 0.f;
+        for (int u = 0; u < US; ++u)
+            dst[u] = ld4(row, (size_t)min((4 * r + w) * 16 * U + 16 * (US * half + u) + 4 * lk, Dv - 4));
+    };
+    // the first steps do not depend on the sample's key count (key tile 0 always exists in memory): they
+    // leave before key_len[b] has arrived
+    load_b(bb[0], 0, 0, 0);
+    load_b(bb[1], 0, 0, 1);
+    load_b(bb[2], 0, 1, 0);
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int j = lane + 64 * u;
-            dsv[t][u] = j < L ? pr[t][u] * (dp[t][u] - r) : 0.f;
-            tsum[t] += dsv[t][u];
+    for (int r = 0; r < ROUNDS; ++r)
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int d = (4 * r + w) * 16 * U + 16 * u + 4 * lk;
+            const float4 x = ld4(dCrow, (size_t)min(d, Dv - 4));
+            a[r][u] = d < Dv ? x : make_float4(0.f, 0.f, 0.f, 0.f);  // columns past Dv add nothing
         }
-    }
-    const float t4 = wave_transpose_sum<4>(tsum);
+    const int L = clamp_len(key_len[b], Tk);
+    const int n_jt = (L + 15) / 16;
+    // the step that the next fetch loads, in the order (key tile, round, half)
+    int f_jt = 0, f_r = 1, f_half = 1;
+    auto fetch = [&](float4 (&dst)[US]) {
+        const bool over = f_jt >= n_jt;
+        load_b(dst, over ? max(n_jt - 1, 0) : f_jt, over ? ROUNDS - 1 : f_r, over ? 1 : f_half);
+        f_half ^= 1;
+        f_r += f_half == 0 ? 1 : 0;
+        f_jt += f_r == ROUNDS ? 1 : 0;
+        f_r = f_r == ROUNDS ? 0 : f_r;
+    };
+    f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int jt = 0; jt < n_jt; ++jt) {           // a key tile is one turn of the four register groups
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const int i = i0 + w + 4 * t;
-        if (i < Tq) {
-            float *ds = dS + ((size_t)b * Tq + i) * pitch;
+        for (int k = 0; k < 4; ++k) {
+            const int r = k >> 1, half = k & 1;
+            fetch(bb[(k + 3) & 3]);
 #pragma unroll
-            for (int u = 0; u < 2; ++u)
-                if (lane + 64 * u < pitch) store_streaming(&ds[lane + 64 * u], dsv[t][u]);
-            if (lane == 16 * t) ds_rowsum[(size_t)b * Tq + i] = t4;
+            for (int u = 0; u < US; ++u) {
+                acc = mfma16(a[r][US * half + u].x, bb[k][u].x, acc);
+                acc = mfma16(a[r][US * half + u].y, bb[k][u].y, acc);
+                acc = mfma16(a[r][US * half + u].z, bb[k][u].z, acc);
+                acc = mfma16(a[r][US * half + u].w, bb[k][u].w, acc);
+            }
         }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) s_dp[w * plane + (4 * lk + q) * pitch16 + jt * 16 + lm] = acc[q];
+        acc = (f32x4){0.f, 0.f, 0.f, 0.f};
     }
+    lds_barrier();
+    dsplit_finish(pr, s_dp, dS, ds_rowsum, b, i0, Tq, L, pitch, pitch16, plane);
 }
 
 // dV of one sample for a 64-wide group of columns and ALL keys: dV[j, n0 .. n0+63] = sum_i P[i, j] dC[i, n0 ..].
@@ -490,14 +611,15 @@ __global__ __launch_bounds__(256, 3) void k_bwd_pre(const float *__restrict__ dC
     if (li < spx * s_tiles) {
         const int b = xcd + kXcd * (li / s_tiles), i0 = (li % s_tiles) * 16;
         if (b >= B) return;
-        if (Tk <= kDsplitMaxTk)
-            dscore_block_dsplit<TV>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
-        else
+        if (Tk <= kDsplitMaxTk) {
+            if (Dv > 512 && Dv <= 1024) dscore_block_dsplit2<TV>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
+            else dscore_block_dsplit<TV>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
+        } else if ((Tk + 15) / 16 > 16 && (Tk + 15) / 16 <= 20) {
             // a wave's key tiles in groups of four, or of five where that takes all of them at once (17 to 20 key tiles)
-            if ((Tk + 15) / 16 > 16 && (Tk + 15) / 16 <= 20)
-                dscore_block<TV, 5>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
-            else
-                dscore_block<TV, 4>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
+            dscore_block<TV, 5>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
+        } else {
+            dscore_block<TV, 4>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
+        }
         return;
     }
     li -= spx * s_tiles;

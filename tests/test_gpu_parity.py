@@ -95,6 +95,12 @@ EDGE = [
     ("ds_sixteen_key_tiles", 1, 17, 256, 64, 8, "f32", [250]),
     ("ds_groups_of_five_key_tiles", 3, 20, 300, 64, 24, "f32", [300, 260, 40]),
     ("ds_groups_of_four_past_twenty_tiles", 2, 10, 330, 64, 8, "f32", [330, 130]),
+    # dS on short key axes: value rows of one round (up to 512 columns), two rounds (up to 1024, ragged) and more;
+    # odd and even numbers of key tiles, a single key tile
+    ("ds_short_keys_one_round_five_tiles", 2, 21, 80, 64, 512, "f32", [80, 33]),
+    ("ds_short_keys_two_rounds_ragged", 3, 21, 40, 64, 600, "f32", [40, 7, 17]),
+    ("ds_short_keys_two_rounds_eight_tiles", 2, 9, 128, 64, 1024, "f32", [128, 97]),
+    ("ds_short_keys_three_rounds", 2, 9, 40, 64, 1100, "f32", [40, 16]),
 ]
 
 
