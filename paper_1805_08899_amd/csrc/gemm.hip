@@ -119,7 +119,7 @@ hipError_t launch_context(const AttnShape &s, const float *P, const void *V, con
 // A lane loads four consecutive d of its row for both operands and spends
 // them on four MFMA steps, so the k index of step c is d0 + 4*(l/16) + c on
 // both sides.
-template <typename TV, int G>
+template <typename TV, int G, int RB>
 __device__ __forceinline__ void dscore_block(const float *__restrict__ dC, const TV *__restrict__ V,
                                              const float *__restrict__ P, const int *__restrict__ key_len,
                                              float *__restrict__ dS, float *__restrict__ ds_rowsum,
@@ -133,20 +133,23 @@ __device__ __forceinline__ void dscore_block(const float *__restrict__ dC, const
     const TV *Vb = V + (size_t)b * Tk * Dv;
 
     // Wave w takes key tiles w, w+4, ..., G at a time so that one fragment of dC feeds G products (the
-    // kernel is bound by what the L1 can deliver, not by the matrix cores); tiles past the sample's last one are
-    // neither loaded nor multiplied.  The sum over d runs in stages of U
-    // 16-wide slices; the loads of the next stage are in flight while the current one is multiplied.  Rows and
-    // keys past the end are clamped for loading; what they produce is never read.  Columns past Dv are zeroed.
+    // kernel is bound by what the L2 can deliver, not by the matrix cores); tiles past the sample's last one are
+    // neither loaded nor multiplied.  RB = 2: the block owns 32 query rows, two fragments of dC, so that every
+    // V fragment feeds two products and the sample's V rows pass through half as many blocks.  The sum over d runs
+    // in stages of U 16-wide slices; the loads of the next stage are in flight while the current one is multiplied.
+    // Rows and keys past the end are clamped for loading; what they produce is never read.  Columns past Dv are zeroed.
     const int n_jt = (L + 15) / 16;
-    constexpr int U = 2;
+    constexpr int U = RB == 2 ? 1 : 2;
     const int n_st = (Dv + 16 * U - 1) / (16 * U);            // stages
     const bool ragged = Dv % (16 * U) != 0;
-    const float *dCrow = dCb + (size_t)min(i0 + lm, Tq - 1) * Dv;
+    const float *dCrow[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) dCrow[rb] = dCb + (size_t)min(i0 + 16 * rb + lm, Tq - 1) * Dv;
     for (int jt0 = w; jt0 < n_jt; jt0 += 4 * G) {              // this wave's tiles jt0, jt0 + 4, jt0 + 8, ...
         const TV *vrow[G];
 #pragma unroll
         for (int k = 0; k < G; ++k) vrow[k] = Vb + (size_t)min((jt0 + 4 * k) * 16 + lm, Tk - 1) * Dv;
-        float4 a[U], bv[G][U], an[U], bn[G][U];
+        float4 a[RB][U], bv[G][U], an[RB][U], bn[G][U];
 #pragma unroll
         for (int k = 0; k < G; ++k)
 #pragma unroll
@@ -155,41 +158,60 @@ __device__ __forceinline__ void dscore_block(const float *__restrict__ dC, const
         bool live[G];
 #pragma unroll
         for (int k = 0; k < G; ++k) live[k] = jt0 + 4 * k < n_jt;
-        auto load = [&](float4 (&da)[U], float4 (&db)[G][U], int st) {
+        auto load = [&](float4 (&da)[RB][U], float4 (&db)[G][U], int st) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int d = min((st * U + u) * 16 + 4 * lk, Dv - 4);
-                da[u] = ld4(dCrow, (size_t)d);
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) da[rb][u] = ld4(dCrow[rb], (size_t)d);
 #pragma unroll
                 for (int k = 0; k < G; ++k)
                     if (live[k]) db[k][u] = ld4(vrow[k], (size_t)d);
             }
         };
         load(a, bv, 0);
-        f32x4 acc[G];
+        f32x4 acc[RB][G];
 #pragma unroll
-        for (int k = 0; k < G; ++k) acc[k] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int k = 0; k < G; ++k) acc[rb][k] = (f32x4){0.f, 0.f, 0.f, 0.f};
         for (int st = 0; st < n_st; ++st) {
             load(an, bn, min(st + 1, n_st - 1));
             if (ragged && st == n_st - 1) {                      // columns past Dv add nothing
 #pragma unroll
                 for (int u = 0; u < U; ++u)
-                    if ((st * U + u) * 16 + 4 * lk >= Dv) a[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if ((st * U + u) * 16 + 4 * lk >= Dv) {
+#pragma unroll
+                        for (int rb = 0; rb < RB; ++rb) a[rb][u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
 #pragma unroll
-                for (int k = 0; k < G; ++k) if (live[k]) acc[k] = mfma16(a[u].x, bv[k][u].x, acc[k]);
+                for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
-                for (int k = 0; k < G; ++k) if (live[k]) acc[k] = mfma16(a[u].y, bv[k][u].y, acc[k]);
+                    for (int k = 0; k < G; ++k) if (live[k]) acc[rb][k] = mfma16(a[rb][u].x, bv[k][u].x, acc[rb][k]);
+                }
 #pragma unroll
-                for (int k = 0; k < G; ++k) if (live[k]) acc[k] = mfma16(a[u].z, bv[k][u].z, acc[k]);
+                for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
-                for (int k = 0; k < G; ++k) if (live[k]) acc[k] = mfma16(a[u].w, bv[k][u].w, acc[k]);
+                    for (int k = 0; k < G; ++k) if (live[k]) acc[rb][k] = mfma16(a[rb][u].y, bv[k][u].y, acc[rb][k]);
+                }
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+                    for (int k = 0; k < G; ++k) if (live[k]) acc[rb][k] = mfma16(a[rb][u].z, bv[k][u].z, acc[rb][k]);
+                }
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+                    for (int k = 0; k < G; ++k) if (live[k]) acc[rb][k] = mfma16(a[rb][u].w, bv[k][u].w, acc[rb][k]);
+                }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                a[u] = an[u];
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) a[rb][u] = an[rb][u];
 #pragma unroll
                 for (int k = 0; k < G; ++k) bv[k][u] = bn[k][u];
             }
@@ -199,17 +221,19 @@ __device__ __forceinline__ void dscore_block(const float *__restrict__ dC, const
             const int jt = jt0 + 4 * k;
             if (jt < n_jt) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) s_dp[(4 * lk + r) * pitch16 + jt * 16 + lm] = acc[k][r];
+                for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) s_dp[(16 * rb + 4 * lk + r) * pitch16 + jt * 16 + lm] = acc[rb][k][r];
             }
         }
     }
-    // P of the four rows this wave finishes, the first NP keys per lane of each: requested together before the
-    // barrier (the registers of the product loop are free by now), where loading row after row inside the loop
-    // below put one trip to memory behind the other
-    constexpr int NP = 5;
-    float pr[4][NP];
+    // P of the rows this wave finishes (w, w + 4, ...), the first NP keys per lane of each: requested together
+    // before the barrier (the registers of the product loop are free by now), where loading row after row inside
+    // the loop below put one trip to memory behind the other
+    constexpr int NP = 5, NR = 4 * RB;
+    float pr[NR][NP];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
+    for (int t = 0; t < NR; ++t) {
         const float *p = P + ((size_t)b * Tq + min(i0 + w + 4 * t, Tq - 1)) * Tk;
 #pragma unroll
         for (int c = 0; c < NP; ++c) pr[t][c] = p[min(lane + 64 * c, Tk - 1)];
@@ -217,7 +241,7 @@ __device__ __forceinline__ void dscore_block(const float *__restrict__ dC, const
     lds_barrier();
 
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
+    for (int t = 0; t < NR; ++t) {
         const int rr = w + 4 * t, i = i0 + rr;
         if (i < Tq) {
             const float *p = P + ((size_t)b * Tq + i) * Tk;
@@ -260,6 +284,7 @@ __device__ __forceinline__ void dscore_block(const float *__restrict__ dC, const
 // are added in wave order by the finishing phase, whose P rows were requested at the very start.
 // Rows and keys past the end are clamped for loading; what they produce is never read.
 constexpr int kDsplitMaxTk = 128;
+constexpr int kDs32MaxTk = 384;      // 32 rows x (Tk + 4) floats: 48.5 KB of LDS at most, three blocks per CU
 
 // The finishing phase of a dS block for short key axes: the four waves' planes of partial dP are added in wave order,
 // then dS = P (dP - sum_j P dP) for rows w, w+4, w+8, w+12 of the tile (pr: their P, two keys per lane).
@@ -592,8 +617,8 @@ __global__ __launch_bounds__(256, 3) void k_bwd_pre(const float *__restrict__ dC
                                                  float *__restrict__ dS, float *__restrict__ ds_rowsum,
                                                  int *__restrict__ order, float *__restrict__ dV, int B, int sorted,
                                                  int fold,
-                                                 int Tq, int Tk, int Dv, int pitch, int s_tiles, int v_groups, int acc) {
-    extern __shared__ float s_dp[];           // [16][pitch16], four such planes when Tk <= kDsplitMaxTk
+                                                 int Tq, int Tk, int Dv, int pitch, int s_tiles, int s_rows, int v_groups, int acc) {
+    extern __shared__ float s_dp[];           // [s_rows][pitch16]; four planes of 16 rows when Tk <= kDsplitMaxTk
     __shared__ int s_len[kMaxSortedB];
     // The hardware deals blocks to the eight XCDs round-robin, so block id mod 8 names the XCD.  Sample b is
     // worked on by XCD b mod 8 only: its dC, V and P then pass through one L2 instead of eight.  Within an XCD the
@@ -609,16 +634,21 @@ __global__ __launch_bounds__(256, 3) void k_bwd_pre(const float *__restrict__ dC
     const int xcd = blockIdx.x % kXcd;
     int li = blockIdx.x / kXcd;
     if (li < spx * s_tiles) {
-        const int b = xcd + kXcd * (li / s_tiles), i0 = (li % s_tiles) * 16;
+        const int b = xcd + kXcd * (li / s_tiles), i0 = (li % s_tiles) * s_rows;
         if (b >= B) return;
         if (Tk <= kDsplitMaxTk) {
             if (Dv > 512 && Dv <= 1024) dscore_block_dsplit2<TV>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
             else dscore_block_dsplit<TV>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
-        } else if ((Tk + 15) / 16 > 16 && (Tk + 15) / 16 <= 20) {
-            // a wave's key tiles in groups of four, or of five where that takes all of them at once (17 to 20 key tiles)
-            dscore_block<TV, 5>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
         } else {
-            dscore_block<TV, 4>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
+            // a wave's key tiles in groups of four, or of five where that takes all of them at once (17 to 20 key tiles)
+            const bool five = (Tk + 15) / 16 > 16 && (Tk + 15) / 16 <= 20;
+            if (s_rows == 32) {
+                if (five) dscore_block<TV, 5, 2>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
+                else dscore_block<TV, 4, 2>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
+            } else {
+                if (five) dscore_block<TV, 5, 1>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
+                else dscore_block<TV, 4, 1>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
+            }
         }
         return;
     }
@@ -638,7 +668,10 @@ hipError_t launch_bwd_pre(const AttnShape &s, const float *dC, const void *V, co
     const int sorted = s.B <= kMaxSortedB ? 1 : 0;
     const int n_hs = (s.H + 63) / 64;
     const int fold = (sorted && (long long)s.B * n_hs <= 512) ? 1 : 0;   // recompute grid in one round
-    const int s_tiles = with_ds ? (s.Tq + 15) / 16 : 0;
+    // dS row tile: 32 rows on long key axes while three such blocks still fit a CU's LDS (the sample's V rows then
+    // pass through half as many blocks), 16 otherwise
+    const int s_rows = (s.Tk > kDsplitMaxTk && s.Tk <= kDs32MaxTk && s.Tq > 16) ? 32 : 16;
+    const int s_tiles = with_ds ? (s.Tq + s_rows - 1) / s_rows : 0;
     // dV blocks per sample.  Short key axes (at most four key tiles, one per wave): a block owns 64 columns and all
     // keys, so its slice of dC is read once (dv_cols_block).  Longer key axes: a block per 16 keys and 256 columns
     // (pv_block); there the all-keys form was measured slower (3 to 12 % of this kernel at workloads 2 and 3: fewer,
@@ -649,7 +682,7 @@ hipError_t launch_bwd_pre(const AttnShape &s, const float *dC, const void *V, co
     const long long blocks = 1 + 8LL * ((s.B + 7) / 8) * (s_tiles + (long long)v_groups);
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     const int pitch16 = (s.Tk + 15) / 16 * 16 + 4;
-    const size_t lds = (size_t)(s.Tk <= kDsplitMaxTk ? 4 : 1) * 16 * pitch16 * sizeof(float);
+    const size_t lds = (size_t)(s.Tk <= kDsplitMaxTk ? 64 : s_rows) * pitch16 * sizeof(float);
 #define ECHO_PRE_LAUNCH(TV, KT)                                                                                     \
     do {                                                                                                            \
         if (lds > 48 * 1024) { /* beyond the default dynamic LDS limit (up to 160 KB per block on gfx950) */        \
@@ -659,7 +692,7 @@ hipError_t launch_bwd_pre(const AttnShape &s, const float *dC, const void *V, co
         }                                                                                                           \
         k_bwd_pre<TV, KT><<<(unsigned)blocks, 256, lds, st>>>(dC, (const TV *)V, P, key_len, dS, ds_rowsum, order, dV, \
                                                              s.B, sorted, fold, s.Tq, s.Tk, s.Dv, ds_pitch(s.Tk),  \
-                                                             s_tiles, v_groups, s.acc ? 1 : 0);                     \
+                                                             s_tiles, s_rows, v_groups, s.acc ? 1 : 0);                     \
     } while (0)
 #define ECHO_PRE_KT(TV)                                 \
     switch (kt) {                                       \

@@ -101,6 +101,12 @@ EDGE = [
     ("ds_short_keys_two_rounds_ragged", 3, 21, 40, 64, 600, "f32", [40, 7, 17]),
     ("ds_short_keys_two_rounds_eight_tiles", 2, 9, 128, 64, 1024, "f32", [128, 97]),
     ("ds_short_keys_three_rounds", 2, 9, 40, 64, 1100, "f32", [40, 16]),
+    # dS on long key axes up to 384 keys: blocks of 32 query rows (ragged last block, fewer than 32 rows in all,
+    # value width not a multiple of 16), 16 rows past 384 keys
+    ("ds_32_row_blocks_ragged", 2, 45, 200, 64, 40, "f32", [200, 131]),
+    ("ds_32_row_blocks_17_rows", 2, 17, 384, 64, 24, "f32", [384, 129]),
+    ("ds_32_row_blocks_bf16", 2, 70, 300, 64, 72, "bf16", [300, 77]),
+    ("ds_16_row_blocks_past_384_keys", 1, 40, 385, 64, 24, "f32", [385]),
 ]
 
 
