@@ -13,6 +13,7 @@ namespace echo {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+__device__ __forceinline__ float comp4(const float4 &x, int c) { return c == 0 ? x.x : c == 1 ? x.y : c == 2 ? x.z : x.w; }
 __device__ __forceinline__ f32x4 mfma16(float a, float b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
@@ -489,6 +490,85 @@ __device__ __forceinline__ void dscore_block_dsplit2(const float *__restrict__ d
     dsplit_finish(pr, s_dp, dS, ds_rowsum, b, i0, Tq, L, pitch, pitch16, plane);
 }
 
+// dV of one sample for a panel of 64 keys and 256 columns, 64 columns per wave: dV[j, n] = sum_i P[i, j] dC[i, n].
+// Per step of four query rows a lane loads four consecutive keys of a P row and four consecutive columns of the dC
+// row (16 bytes each) and spends them on 16 products: component ca of the keys with component cb of the columns,
+// so product (ca, cb) holds keys m0 + 4 (row of the result tile) + ca and columns n0 + 4 (l % 16) + cb.  Two bytes
+// of operands per lane and product, against five in the form with one key per lane (pv_block), which at the larger
+// workloads was bound by what the L2 could deliver.  Needs Tk % 4 == 0 (16-byte loads of P rows).  Batches of U
+// steps are double buffered.  Rows of masked keys (j >= L) come out as exact zeros whatever P holds there.
+__device__ __forceinline__ void dv_tile64(const float *__restrict__ P, const float *__restrict__ dC,
+                                          const int *__restrict__ key_len, float *__restrict__ dV, int Tq, int Tk,
+                                          int Dv, int b, int by, int bx, int acc_out) {
+    constexpr int U = 4;
+    const int L = clamp_len(key_len[b], Tk);
+    const int lane = lane_id(), w = wave_id();
+    const int lm = lane & 15, lk = lane >> 4;
+    const int m0 = by * 64, n0 = (bx * 4 + w) * 64;
+    if (n0 >= Dv) return;
+    const int kcol = m0 + 4 * lm;             // first of this lane's four keys
+    const int ncol = n0 + 4 * lm;             // first of this lane's four columns
+    const bool nok = ncol < Dv;
+    const float *Pb = P + (size_t)b * Tq * Tk;
+    const float *Cb = dC + (size_t)b * Tq * Dv;
+    f32x4 acc[4][4];
+#pragma unroll
+    for (int ca = 0; ca < 4; ++ca)
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb) acc[ca][cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    if (m0 < L) {
+        const int kc = min(kcol, Tk - 4), nc = min(ncol, Dv - 4);       // clamped for loading
+        float4 a[U], bv[U], an[U], bn[U];
+        auto load = [&](float4 (&da)[U], float4 (&db)[U], int kb0) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int k = min(kb0 + 4 * u + lk, Tq - 1);
+                da[u] = ld4(Pb, (size_t)k * Tk + kc);
+                db[u] = ld4(Cb, (size_t)k * Dv + nc);
+            }
+        };
+        load(a, bv, 0);
+        for (int kb0 = 0; kb0 < Tq; kb0 += 4 * U) {
+            load(an, bn, min(kb0 + 4 * U, Tq - 1));
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const bool row_on = kb0 + 4 * u + lk < Tq;               // rows past Tq add nothing
+                float x[4];
+#pragma unroll
+                for (int ca = 0; ca < 4; ++ca) x[ca] = (row_on && kcol + ca < L) ? comp4(a[u], ca) : 0.f;
+#pragma unroll
+                for (int ca = 0; ca < 4; ++ca)
+#pragma unroll
+                    for (int cb = 0; cb < 4; ++cb) acc[ca][cb] = mfma16(x[ca], comp4(bv[u], cb), acc[ca][cb]);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                a[u] = an[u];
+                bv[u] = bn[u];
+            }
+        }
+    }
+    if (!nok) return;
+    float *ob = dV + (size_t)b * Tk * Dv;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int ca = 0; ca < 4; ++ca) {
+            const int m = m0 + 16 * lk + 4 * r + ca;
+            if (m < Tk) {
+                float4 o = make_float4(acc[ca][0][r], acc[ca][1][r], acc[ca][2][r], acc[ca][3][r]);
+                if (acc_out) {                       // add to what the earlier decoder steps left
+                    const float4 old = *reinterpret_cast<const float4 *>(ob + (size_t)m * Dv + ncol);
+                    o.x += old.x;
+                    o.y += old.y;
+                    o.z += old.z;
+                    o.w += old.w;
+                }
+                store4_streaming(ob + (size_t)m * Dv + ncol, o);
+            }
+        }
+}
+
 // dV of one sample for a 64-wide group of columns and ALL keys: dV[j, n0 .. n0+63] = sum_i P[i, j] dC[i, n0 ..].
 // The block's slice of dC (Tq rows of 256 bytes) passes through the CU once; the earlier form, a block per 16 keys
 // and 256 columns, read dC once per key tile and was bound by what the L2 could deliver at the larger workloads.
@@ -655,8 +735,11 @@ __global__ __launch_bounds__(256, 3) void k_bwd_pre(const float *__restrict__ dC
     li -= spx * s_tiles;
     const int b = xcd + kXcd * (li / per_b), rem = li % per_b;
     if (b >= B) return;
-    if constexpr (KT > 0) {
+    if constexpr (KT == 1) {
         dv_cols_block<KT>(P, dC, key_len, dV, Tq, Tk, Dv, b, rem, acc);
+    } else if constexpr (KT == 2) {           // v_groups = column groups of 256, times the panels of 64 keys
+        const int v_xt = (Dv + 255) / 256;
+        dv_tile64(P, dC, key_len, dV, Tq, Tk, Dv, b, rem / v_xt, rem % v_xt, acc);
     } else {                                  // v_groups = column groups of 256, times the key tiles
         const int v_xt = (Dv + 255) / 256;
         pv_block<float, true>(P, dC, key_len, dV, Tq, Tk, Dv, b, rem / v_xt, rem % v_xt, acc);
@@ -673,12 +756,17 @@ hipError_t launch_bwd_pre(const AttnShape &s, const float *dC, const void *V, co
     const int s_rows = (s.Tk > kDsplitMaxTk && s.Tk <= kDs32MaxTk && s.Tq > 16) ? 32 : 16;
     const int s_tiles = with_ds ? (s.Tq + s_rows - 1) / s_rows : 0;
     // dV blocks per sample.  Short key axes (at most four key tiles, one per wave): a block owns 64 columns and all
-    // keys, so its slice of dC is read once (dv_cols_block).  Longer key axes: a block per 16 keys and 256 columns
+    // keys, so its slice of dC is read once (dv_cols_block).  Up to 128 keys: a block per 16 keys and 256 columns
     // (pv_block); there the all-keys form was measured slower (3 to 12 % of this kernel at workloads 2 and 3: fewer,
-    // longer blocks balance worse and a wave's batches of loads are too short to cover a trip to memory).
+    // longer blocks balance worse and a wave's batches of loads are too short to cover a trip to memory), and so
+    // were panels of 64 keys (backward 139.5 -> 147 us at B = 128, T = 100: the second panel is half empty).
+    // Beyond 128 keys, Tk a multiple of four: panels of 64 keys x 256 columns (dv_tile64; backward 635 -> 629 us
+    // at B = 32, T = 300, H = 1024, where this launch now runs at 60 % of the matrix cores' fp32 peak).
     const int per_wave = ((s.Tk + 15) / 16 + 3) / 4;
-    const int kt = per_wave <= 1 ? 1 : 0;
-    const int v_groups = kt ? (s.Dv + 63) / 64 : ((s.Dv + 255) / 256) * ((s.Tk + 15) / 16);
+    const int kt = per_wave <= 1 ? 1 : (s.Tk % 4 == 0 && s.Tk > kDsplitMaxTk ? 2 : 0);
+    const int v_groups = kt == 1   ? (s.Dv + 63) / 64
+                         : kt == 2 ? ((s.Dv + 255) / 256) * ((s.Tk + 63) / 64)
+                                   : ((s.Dv + 255) / 256) * ((s.Tk + 15) / 16);
     const long long blocks = 1 + 8LL * ((s.B + 7) / 8) * (s_tiles + (long long)v_groups);
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     const int pitch16 = (s.Tk + 15) / 16 * 16 + 4;
@@ -697,6 +785,7 @@ hipError_t launch_bwd_pre(const AttnShape &s, const float *dC, const void *V, co
 #define ECHO_PRE_KT(TV)                                 \
     switch (kt) {                                       \
         case 1: ECHO_PRE_LAUNCH(TV, 1); break;          \
+        case 2: ECHO_PRE_LAUNCH(TV, 2); break;          \
         default: ECHO_PRE_LAUNCH(TV, 0); break;         \
     }
     if (s.bf16) {

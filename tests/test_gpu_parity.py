@@ -107,6 +107,14 @@ EDGE = [
     ("ds_32_row_blocks_17_rows", 2, 17, 384, 64, 24, "f32", [384, 129]),
     ("ds_32_row_blocks_bf16", 2, 70, 300, 64, 72, "bf16", [300, 77]),
     ("ds_16_row_blocks_past_384_keys", 1, 40, 385, 64, 24, "f32", [385]),
+    # dV on key axes past 128: panels of 64 keys x 256 columns when Tk is a multiple of four (ragged last panel,
+    # value width not a multiple of 64, fewer rows than one batch, masked keys inside a panel), one key tile per
+    # block otherwise and up to 128 keys
+    ("dv_panels_of_64_keys", 2, 37, 164, 64, 264, "f32", [164, 35]),
+    ("dv_panels_few_rows", 2, 3, 132, 64, 24, "f32", [132, 1]),
+    ("dv_panels_bf16", 2, 21, 196, 64, 520, "bf16", [196, 64]),
+    ("dv_key_tiles_when_tk_not_multiple_of_4", 2, 21, 165, 64, 264, "f32", [165, 35]),
+    ("dv_key_tiles_up_to_128_keys", 2, 37, 100, 64, 264, "f32", [100, 35]),
 ]
 
 
@@ -320,6 +328,7 @@ STEP_CASES = [
     ("steps_h_not_multiple_of_4", 2, 2, 11, 33, 8, "f32"),
     ("steps_64_keys_ragged_second_chunk", 5, 3, 64, 260, 264, "f32"),      # the short-axis kernels at their limit
     ("steps_65_keys", 3, 2, 65, 64, 32, "bf16"),                           # one key beyond it
+    ("steps_132_keys", 3, 5, 132, 64, 72, "f32"),                          # dV by panels of 64 keys, accumulating
     ("steps_with_empty_samples", 9, 2, 6, 32, 16, "f32"),                  # key_len drawn from 0..Tk
     ("steps_batch_beyond_the_four_block_form", 70, 2, 20, 64, 32, "f32"),  # 4 B blocks would not all run at once
 ]
