@@ -21,7 +21,8 @@
 //   C  the waves normalise the rows (softmax over the valid keys) and write P.
 //   D  context = P V on the matrix cores: v_mfma_f32_4x4x1 treats the 64 lanes
 //      as 16 column groups of 4, so a lane owns one output column and reads V
-//      rows with plain coalesced loads.
+//      rows with plain coalesced loads (in batches of rows, one batch ahead; all rows at once,
+//      before the softmax, when the key axis is short: ContextAllRows).
 //
 // A block's whole pass is short compared with a trip to memory, so loads are
 // issued well before they are consumed: the first key slice leaves before the
@@ -495,6 +496,64 @@ struct ContextPhase {
     }
 };
 
+// The context phase for short key axes (at most 64 keys) and at most one group of 64 columns per wave: a lane owns
+// one column and requests ALL value rows of it at once, before the softmax, so that they arrive while the block waits
+// for its last scores and normalises them; the products then find their operands in registers.  (With batches of
+// 16 rows one ahead every further batch was a trip to memory that the 32 products of the batch before could not
+// cover: 1.4 us for a block with 16 keys, 3.1 us for one with 50.)
+template <typename T, int RT>
+struct ContextAllRows {
+    static constexpr int NR4 = RT / 4;
+    float v[4][16];
+    __device__ __forceinline__ void start(const T *vb, int Dv, int L, int lane, int w) {
+        const int n = min(w * 64 + lane, Dv - 1);
+        const int Lp = (L + 3) & ~3;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            if (16 * g < Lp) {                                   // uniform
+#pragma unroll
+                for (int kk = 0; kk < 16; ++kk) v[g][kk] = ld(vb, (size_t)(unsigned)(min(16 * g + kk, L - 1) * Dv + n));
+            } else {
+#pragma unroll
+                for (int kk = 0; kk < 16; ++kk) v[g][kk] = 0.f;
+            }
+        }
+    }
+    __device__ __forceinline__ void run(const float *s_S, int spitch, float *Cb, int Dv, int Lp, int ni, int lane,
+                                        int w) {
+        const int n = w * 64 + lane;
+        if (w * 64 >= Dv) return;                                // a wave without columns (uniform)
+        const int lr = lane & 3;
+        f32x4 acc[NR4];
+#pragma unroll
+        for (int t = 0; t < NR4; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+#pragma unroll
+            for (int k4 = 0; k4 < 16; k4 += 4) {
+                if (16 * g + k4 < Lp) {                          // uniform
+                    float4 pr[NR4];
+#pragma unroll
+                    for (int t = 0; t < NR4; ++t)
+                        pr[t] = *reinterpret_cast<const float4 *>(s_S + (4 * t + lr) * spitch + 16 * g + k4);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+#pragma unroll
+                        for (int t = 0; t < NR4; ++t)
+                            acc[t] = __builtin_amdgcn_mfma_f32_4x4x1f32(comp(pr[t], q), v[g][k4 + q], acc[t], 0, 0, 0);
+                }
+            }
+        }
+        if (n < Dv) {
+#pragma unroll
+            for (int t = 0; t < NR4; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (4 * t + r < ni) store_streaming(&Cb[(size_t)(4 * t + r) * Dv + n], acc[t][r]);
+        }
+    }
+};
+
 // Which (sample, row tile) this block works on and the sample's valid keys; see "Placement" at the top.
 // Ranked mode: wave 0 finds the sample that holds a given rank by radix selection over composite keys
 // (valid keys, then index) held two per lane, and hands the answer to the other waves through s_pick.
@@ -769,7 +828,12 @@ __global__ __launch_bounds__(64 * W, NG == 1 ? 4 : 2) void k_fwd_fused(
         }
         lds_barrier();
     };
-    if (Dv >= 1024) {                                           // at least four waves with columns to work on
+    if (ROWMODE && Tk <= 64 && Dv <= 64 * W) {                  // all value rows of a wave's columns at once
+        ContextAllRows<T, RT> cp;
+        cp.start(vb, Dv, L, lane, w);
+        softmax();
+        cp.run(s_S, spitch, Cb, Dv, Lp, ni, lane, w);
+    } else if (Dv >= 1024) {                                    // at least four waves with columns to work on
         ContextPhase<T, RT, 4> cp;
         cp.start(vb, Dv, L, lane, w);
         softmax();
