@@ -407,22 +407,33 @@ __device__ __forceinline__ void dscore_block_dsplit(const float *__restrict__ dC
     dsplit_finish(pr, s_dp, dS, ds_rowsum, b, i0, Tq, L, pitch, pitch16, plane);
 }
 
-// Value rows of 513 to 1024 columns (two rounds): the wave's slices of the 16 dC rows for both rounds stay in
-// registers for the whole block (the general form above fetches them again for every key tile and round and waits
-// for them each time), and the V slices arrive as a stream of steps (key tile, round, half): four 16-byte loads per
-// lane each, held in four register groups used in turn, so that three steps are under way while one is multiplied.
-// Past the last step the stream repeats it.  Measured at B = 128, T = 50, Dv = 1024: backward 92.0 -> 87.6 us.  (For
-// one round, where dC is kept already, the finer stream measured 1 % slower than two groups of a whole round.)
-template <typename TV>
-__device__ __forceinline__ void dscore_block_dsplit2(const float *__restrict__ dC, const TV *__restrict__ V,
-                                                    const float *__restrict__ P, const int *__restrict__ key_len,
-                                                    float *__restrict__ dS, float *__restrict__ ds_rowsum,
-                                                    float *__restrict__ s_dp, int b, int i0, int Tq, int Tk,
-                                                    int Dv, int pitch) {
+// Value rows of at most 512 columns (one round), operands through LDS.  A quarter of a wave that reads the operand
+// layout of the matrix cores straight from memory asks for the same 16 bytes of 16 different rows; with rows a
+// multiple of 128 bytes apart these requests queue in the CU's L1 (measured: 37 KB/us per CU, against 90 to 110
+// for loads of whole row pieces, and 67 with rows 2064 bytes apart).  Here a wave loads its 128 columns of 16 rows
+// as 8 loads of two 512-byte row pieces each (lanes along d), writes them row by row into its own 16 x 132 floats
+// of LDS and reads them back in operand layout (row l % 16, 16 bytes at column 16 u + 4 (l / 16): conflict-free at
+// this pitch).  The region belongs to one wave, so no barrier is involved; the V slice of the next key tile is in
+// flight in registers while the current one is multiplied.  The partial dP tiles stay in registers until the end and
+// then go into the same region, which the finishing phase reads as the wave's plane.
+constexpr int kStagePitch = 132;                 // floats; 16 rows of it are a wave's region
+// ROUNDS = 2: value rows of 513 to 1024 columns; the dC slices of both rounds stay in registers, the steps run over
+// (key tile, round), and the partial dP tiles go to planes of their own behind the staging regions as each key tile
+// finishes (there is no room to keep eight of them in registers next to two rounds of dC).
+template <typename TV, int ROUNDS>
+__device__ __forceinline__ void dscore_block_dsplit_lds(const float *__restrict__ dC, const TV *__restrict__ V,
+                                                        const float *__restrict__ P, const int *__restrict__ key_len,
+                                                        float *__restrict__ dS, float *__restrict__ ds_rowsum,
+                                                        float *__restrict__ s_stage, int b, int i0, int Tq, int Tk,
+                                                        int Dv, int pitch) {
     const int lane = lane_id(), w = wave_id();
     const int lm = lane & 15, lk = lane >> 4;
     const int pitch16 = (Tk + 15) / 16 * 16 + 4;
-    const int plane = 16 * pitch16;
+    constexpr int region = 16 * kStagePitch;
+    constexpr int NT = ROUNDS == 1 ? kDsplitMaxTk / 16 : 1;       // dP tiles kept in registers
+    // the planes of partial dP: the staging regions themselves (one round) or planes behind them
+    float *planes = ROUNDS == 1 ? s_stage : s_stage + 4 * region;
+    const int plane = ROUNDS == 1 ? region : 16 * pitch16;
     // P of the rows this wave finishes (rows w, w+4, w+8, w+12 of the tile), two keys per lane
     float pr[4][2];
 #pragma unroll
@@ -431,63 +442,80 @@ __device__ __forceinline__ void dscore_block_dsplit2(const float *__restrict__ d
 #pragma unroll
         for (int u = 0; u < 2; ++u) pr[t][u] = P[((size_t)b * Tq + i) * Tk + min(lane + 64 * u, Tk - 1)];
     }
-    const float *dCrow = dC + ((size_t)b * Tq + min(i0 + lm, Tq - 1)) * Dv;
-    const TV *Vb = V + (size_t)b * Tk * Dv;
-    constexpr int ROUNDS = 2;
     constexpr int U = 8;                          // 16-wide slices of d per wave and round
-    constexpr int US = 4;                         // slices per step
-    float4 a[ROUNDS][U], bb[4][US];
-    auto load_b = [&](float4 (&dst)[US], int jt, int r, int half) {
-        const TV *row = Vb + (size_t)min(jt * 16 + lm, Tk - 1) * Dv;
+    float *st = s_stage + w * region;             // this wave's region
+    const int cr = lane >> 5, cc = 4 * (lane & 31);               // loading: row of the pair, column in the chunk
+    const float *dCb = dC + (size_t)b * Tq * Dv;
+    const TV *Vb = V + (size_t)b * Tk * Dv;
+    float4 a[ROUNDS][U], bcur[U], bnxt[U];
+    auto col_of = [&](int r) { return min((4 * r + w) * 16 * U + cc, Dv - 4); };   // clamped for loading
+    auto load_v = [&](float4 (&dst)[U], int it) {                 // step it = (key tile, round): 16 keys, two per load
+        const int jt = it / ROUNDS, r = it % ROUNDS;
+        const int col = col_of(r);
 #pragma unroll
-        for (int u = 0; u < US; ++u)
-            dst[u] = ld4(row, (size_t)min((4 * r + w) * 16 * U + 16 * (US * half + u) + 4 * lk, Dv - 4));
+        for (int u = 0; u < U; ++u) dst[u] = ld4(Vb + (size_t)min(jt * 16 + 2 * u + cr, Tk - 1) * Dv, (size_t)col);
     };
-    // the first steps do not depend on the sample's key count (key tile 0 always exists in memory): they
-    // leave before key_len[b] has arrived
-    load_b(bb[0], 0, 0, 0);
-    load_b(bb[1], 0, 0, 1);
-    load_b(bb[2], 0, 1, 0);
+    auto through_lds = [&](float4 (&dst)[U], const float4 (&src)[U]) {
 #pragma unroll
-    for (int r = 0; r < ROUNDS; ++r)
+        for (int u = 0; u < U; ++u) *reinterpret_cast<float4 *>(st + (2 * u + cr) * kStagePitch + cc) = src[u];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int d = (4 * r + w) * 16 * U + 16 * u + 4 * lk;
-            const float4 x = ld4(dCrow, (size_t)min(d, Dv - 4));
-            a[r][u] = d < Dv ? x : make_float4(0.f, 0.f, 0.f, 0.f);  // columns past Dv add nothing
-        }
+        for (int u = 0; u < U; ++u) dst[u] = *reinterpret_cast<const float4 *>(st + lm * kStagePitch + 16 * u + 4 * lk);
+    };
+    // the first loads do not depend on the sample's key count (key tile 0 always exists in memory)
+    load_v(bnxt, 0);
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) {
+        const int col = col_of(r);
+#pragma unroll
+        for (int u = 0; u < U; ++u) a[r][u] = ld4(dCb + (size_t)min(i0 + 2 * u + cr, Tq - 1) * Dv, (size_t)col);
+    }
     const int L = clamp_len(key_len[b], Tk);
     const int n_jt = (L + 15) / 16;
-    // the step that the next fetch loads, in the order (key tile, round, half)
-    int f_jt = 0, f_r = 1, f_half = 1;
-    auto fetch = [&](float4 (&dst)[US]) {
-        const bool over = f_jt >= n_jt;
-        load_b(dst, over ? max(n_jt - 1, 0) : f_jt, over ? ROUNDS - 1 : f_r, over ? 1 : f_half);
-        f_half ^= 1;
-        f_r += f_half == 0 ? 1 : 0;
-        f_jt += f_r == ROUNDS ? 1 : 0;
-        f_r = f_r == ROUNDS ? 0 : f_r;
-    };
-    f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
-    for (int jt = 0; jt < n_jt; ++jt) {           // a key tile is one turn of the four register groups
+    const int items = n_jt * ROUNDS;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int r = k >> 1, half = k & 1;
-            fetch(bb[(k + 3) & 3]);
+    for (int r = 0; r < ROUNDS; ++r) {
+        through_lds(a[r], a[r]);
 #pragma unroll
-            for (int u = 0; u < US; ++u) {
-                acc = mfma16(a[r][US * half + u].x, bb[k][u].x, acc);
-                acc = mfma16(a[r][US * half + u].y, bb[k][u].y, acc);
-                acc = mfma16(a[r][US * half + u].z, bb[k][u].z, acc);
-                acc = mfma16(a[r][US * half + u].w, bb[k][u].w, acc);
+        for (int u = 0; u < U; ++u)                               // columns past Dv add nothing
+            if ((4 * r + w) * 16 * U + 16 * u + 4 * lk >= Dv) a[r][u] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    through_lds(bcur, bnxt);
+    f32x4 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int jt = 0; jt < kDsplitMaxTk / 16; ++jt) {
+        if (jt < n_jt) {                                           // uniform
+#pragma unroll
+            for (int r = 0; r < ROUNDS; ++r) {
+                load_v(bnxt, min(jt * ROUNDS + r + 1, max(items - 1, 0)));
+                f32x4 &d = acc[ROUNDS == 1 ? jt : 0];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    d = mfma16(a[r][u].x, bcur[u].x, d);
+                    d = mfma16(a[r][u].y, bcur[u].y, d);
+                    d = mfma16(a[r][u].z, bcur[u].z, d);
+                    d = mfma16(a[r][u].w, bcur[u].w, d);
+                }
+                through_lds(bcur, bnxt);
+            }
+            if (ROUNDS > 1) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) planes[w * plane + (4 * lk + q) * pitch16 + jt * 16 + lm] = acc[0][q];
+                acc[0] = (f32x4){0.f, 0.f, 0.f, 0.f};
             }
         }
+    }
+    if (ROUNDS == 1) {                            // the wave's plane of partial dP into its own region
 #pragma unroll
-        for (int q = 0; q < 4; ++q) s_dp[w * plane + (4 * lk + q) * pitch16 + jt * 16 + lm] = acc[q];
-        acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int jt = 0; jt < kDsplitMaxTk / 16; ++jt)
+            if (jt < n_jt) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) st[(4 * lk + q) * pitch16 + jt * 16 + lm] = acc[ROUNDS == 1 ? jt : 0][q];
+            }
     }
     lds_barrier();
-    dsplit_finish(pr, s_dp, dS, ds_rowsum, b, i0, Tq, L, pitch, pitch16, plane);
+    dsplit_finish(pr, planes, dS, ds_rowsum, b, i0, Tq, L, pitch, pitch16, plane);
 }
 
 // dV of one sample for a panel of 64 keys and 256 columns, 64 columns per wave: dV[j, n] = sum_i P[i, j] dC[i, n].
@@ -717,7 +745,8 @@ __global__ __launch_bounds__(256, 3) void k_bwd_pre(const float *__restrict__ dC
         const int b = xcd + kXcd * (li / s_tiles), i0 = (li % s_tiles) * s_rows;
         if (b >= B) return;
         if (Tk <= kDsplitMaxTk) {
-            if (Dv > 512 && Dv <= 1024) dscore_block_dsplit2<TV>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
+            if (Dv <= 512) dscore_block_dsplit_lds<TV, 1>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
+            else if (Dv <= 1024) dscore_block_dsplit_lds<TV, 2>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
             else dscore_block_dsplit<TV>(dC, V, P, key_len, dS, ds_rowsum, s_dp, b, i0, Tq, Tk, Dv, pitch);
         } else {
             // a wave's key tiles in groups of four, or of five where that takes all of them at once (17 to 20 key tiles)
@@ -770,7 +799,12 @@ hipError_t launch_bwd_pre(const AttnShape &s, const float *dC, const void *V, co
     const long long blocks = 1 + 8LL * ((s.B + 7) / 8) * (s_tiles + (long long)v_groups);
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     const int pitch16 = (s.Tk + 15) / 16 * 16 + 4;
-    const size_t lds = (size_t)(s.Tk <= kDsplitMaxTk ? 64 : s_rows) * pitch16 * sizeof(float);
+    // short key axes: four planes of 16 rows, or (one round over d) the four waves' staging regions, which the
+    // planes then share
+    const size_t lds = s.Tk > kDsplitMaxTk ? (size_t)s_rows * pitch16 * sizeof(float)
+                       : s.Dv <= 512       ? (size_t)4 * 16 * kStagePitch * sizeof(float)
+                       : s.Dv <= 1024      ? (size_t)(4 * 16 * kStagePitch + 64 * pitch16) * sizeof(float)
+                                           : (size_t)64 * pitch16 * sizeof(float);
 #define ECHO_PRE_LAUNCH(TV, KT)                                                                                     \
     do {                                                                                                            \
         if (lds > 48 * 1024) { /* beyond the default dynamic LDS limit (up to 160 KB per block on gfx950) */        \
