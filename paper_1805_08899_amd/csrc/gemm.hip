@@ -407,19 +407,21 @@ __device__ __forceinline__ void dscore_block_dsplit(const float *__restrict__ dC
     dsplit_finish(pr, s_dp, dS, ds_rowsum, b, i0, Tq, L, pitch, pitch16, plane);
 }
 
-// Value rows of at most 512 columns (one round), operands through LDS.  A quarter of a wave that reads the operand
+// Short key axes, value rows of at most 1024 columns, operands through LDS.  A quarter of a wave that reads the operand
 // layout of the matrix cores straight from memory asks for the same 16 bytes of 16 different rows; with rows a
 // multiple of 128 bytes apart these requests queue in the CU's L1 (measured: 37 KB/us per CU, against 90 to 110
 // for loads of whole row pieces, and 67 with rows 2064 bytes apart).  Here a wave loads its 128 columns of 16 rows
 // as 8 loads of two 512-byte row pieces each (lanes along d), writes them row by row into its own 16 x 132 floats
 // of LDS and reads them back in operand layout (row l % 16, 16 bytes at column 16 u + 4 (l / 16): conflict-free at
 // this pitch).  The region belongs to one wave, so no barrier is involved; the V slice of the next key tile is in
-// flight in registers while the current one is multiplied.  The partial dP tiles stay in registers until the end and
-// then go into the same region, which the finishing phase reads as the wave's plane.
+// flight in registers while the current one is multiplied.
+// ROUNDS = 1 (up to 512 columns): the partial dP tiles stay in registers until the end and then go into the same
+// region, which the finishing phase reads as the wave's plane.
+// ROUNDS = 2 (513 to 1024 columns): the dC slices of both rounds stay in registers, the steps run over (key tile,
+// round), and the partial dP tiles go to planes of their own behind the staging regions as each key tile finishes
+// (there is no room to keep eight of them in registers next to two rounds of dC).  The general form above fetches
+// the dC slices again for every key tile and round and waits for them each time.
 constexpr int kStagePitch = 132;                 // floats; 16 rows of it are a wave's region
-// ROUNDS = 2: value rows of 513 to 1024 columns; the dC slices of both rounds stay in registers, the steps run over
-// (key tile, round), and the partial dP tiles go to planes of their own behind the staging regions as each key tile
-// finishes (there is no room to keep eight of them in registers next to two rounds of dC).
 template <typename TV, int ROUNDS>
 __device__ __forceinline__ void dscore_block_dsplit_lds(const float *__restrict__ dC, const TV *__restrict__ V,
                                                         const float *__restrict__ P, const int *__restrict__ key_len,
