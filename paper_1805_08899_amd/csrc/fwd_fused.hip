@@ -885,8 +885,17 @@ static hipError_t launch_fwd_fused_t(const AttnShape &s, const void *Qp, const v
         hipError_t e = ensure_dynamic_lds((const void *)k_fwd_fused<T, NG, ROWNS, W>, lds, granted);
         if (e != hipSuccess) return e;
     }
-    const int tiles = (s.Tq + RT - 1) / RT;
+    int tiles = (s.Tq + RT - 1) / RT;
     const int samples_per_xcd = (s.B + FW_XCD - 1) / FW_XCD;
+    // Row mode with less than one round of blocks (two per CU): more, smaller row tiles while the grid still fits
+    // the round, so that every CU holds a heavy and a light tile (with 448 blocks 64 CUs held a single heavy one and
+    // the fullest CU 18 % more keys than the average; with 512 it is 5 %; the keys are exponentiated once more per sample).
+    // At most twice the tiles (at least RT / 2 rows each).
+    // (Streaming mode loses with smaller tiles: 74 -> 82 us at B = 128, T = 100, where whole rounds were filled that way.)
+    if (ROWNS > 0 && W == FW_W) {
+        const int most = min(s.Tq, 2 * tiles);
+        while (tiles < most && (long long)FW_XCD * samples_per_xcd * (tiles + 1) <= 2 * FW_XCD * FW_CU_PER_XCD) ++tiles;
+    }
     const long long grid = (long long)FW_XCD * samples_per_xcd * tiles;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     const int ranked = s.B <= FW_MAX_RANKED_B ? 1 : 0;
