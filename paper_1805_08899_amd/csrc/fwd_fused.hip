@@ -443,13 +443,15 @@ struct ContextPhase {
 #pragma unroll
             for (int t = 0; t < NR4; ++t) acc[c][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
         int g = w, kb0 = 0;
-        while (g < n_grp) {
+        // one batch of value rows: products of `cur`, whose successor goes into `nxt` meanwhile; the two register
+        // groups change roles from batch to batch (no copies)
+        auto batch = [&](float (&cur)[KB][CPL], float (&nxt)[KB][CPL]) {
             int g2 = g, kb2 = kb0 + KB;
             if (kb2 >= Lp) {
                 g2 = g + n_waves;
                 kb2 = 0;
             }
-            fetch(vnxt, vb, Dv, L, lane, min(g2, n_grp - 1), kb2);
+            fetch(nxt, vb, Dv, L, lane, min(g2, n_grp - 1), kb2);
 #pragma unroll
             for (int k4 = 0; k4 < KB; k4 += 4) {
                 if (kb0 + k4 < Lp) {
@@ -463,7 +465,7 @@ struct ContextPhase {
                         for (int c = 0; c < CPL; ++c)
 #pragma unroll
                             for (int t = 0; t < NR4; ++t)
-                                acc[c][t] = __builtin_amdgcn_mfma_f32_4x4x1f32(comp(pr[t], q), vcur[k4 + q][c],
+                                acc[c][t] = __builtin_amdgcn_mfma_f32_4x4x1f32(comp(pr[t], q), cur[k4 + q][c],
                                                                                acc[c][t], 0, 0, 0);
                 }
             }
@@ -486,12 +488,13 @@ struct ContextPhase {
 #pragma unroll
                     for (int t = 0; t < NR4; ++t) acc[c][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
             }
-#pragma unroll
-            for (int kk = 0; kk < KB; ++kk)
-#pragma unroll
-                for (int c = 0; c < CPL; ++c) vcur[kk][c] = vnxt[kk][c];
             g = g2;
             kb0 = kb2;
+        };
+        while (g < n_grp) {
+            batch(vcur, vnxt);
+            if (g >= n_grp) break;
+            batch(vnxt, vcur);
         }
     }
 };
