@@ -22,7 +22,8 @@
 //   D  context = P V on the matrix cores: v_mfma_f32_4x4x1 treats the 64 lanes
 //      as 16 column groups of 4, so a lane owns one output column and reads V
 //      rows with plain coalesced loads (in batches of rows, one batch ahead; all rows at once,
-//      before the softmax, when the key axis is short: ContextAllRows).
+//      before the softmax, when the key axis is short: ContextAllRows; two waves per group of 256
+//      columns with half of the keys each when there are twice as many waves as groups: ContextSplitKeys).
 //
 // A block's whole pass is short compared with a trip to memory, so loads are
 // issued well before they are consumed: the first key slice leaves before the
@@ -499,6 +500,91 @@ struct ContextPhase {
     }
 };
 
+// The context phase when at least half of the waves would have no columns (value rows of 256 columns per wave, eight
+// waves, Dv = 1024): two waves share a column group and take half of the keys each, so that all waves have loads under
+// way; the second wave's partial tile reaches the first through LDS (s_x: RT x Dv floats that nobody reads any more, the
+// staged query rows), which adds it and writes the context rows.
+template <typename T, int RT>
+struct ContextSplitKeys {
+    static constexpr int CPL = 4, KB = 8, NR4 = RT / 4;
+    float vcur[KB][CPL], vnxt[KB][CPL];
+    int g, half, k0, k1;                // column group, which half of the keys, keys k0 .. k1 - 1 (multiples of 4)
+
+    __device__ __forceinline__ void fetch(float (&dst)[KB][CPL], const T *vb, int Dv, int L, int lane, int kb0) {
+        const int n = min((g * 64 + lane) * CPL, Dv - CPL);
+#pragma unroll
+        for (int kk = 0; kk < KB; ++kk)
+            ColVec<CPL>::load(vb, (size_t)(unsigned)(min(kb0 + kk, L - 1) * Dv + n), dst[kk]);
+    }
+    __device__ __forceinline__ void start(const T *vb, int Dv, int L, int Lp, int lane, int w) {
+        const int n_grp = (Dv + 64 * CPL - 1) / (64 * CPL);
+        g = w % n_grp;
+        half = w / n_grp;
+        const int Lh = ((Lp / 4 + 1) / 2) * 4;
+        k0 = half == 0 ? 0 : half == 1 ? Lh : Lp;                // waves past the second half (if any) have no keys
+        k1 = half == 0 ? Lh : Lp;
+        if (k0 < k1) fetch(vcur, vb, Dv, L, lane, k0);
+    }
+    __device__ __forceinline__ void run(const T *vb, const float *s_S, int spitch, float *s_x, float *Cb, int Dv, int L,
+                                        int ni, int lane) {
+        const int lr = lane & 3;
+        f32x4 acc[CPL][NR4];
+#pragma unroll
+        for (int c = 0; c < CPL; ++c)
+#pragma unroll
+            for (int t = 0; t < NR4; ++t) acc[c][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        int kb0 = k0;
+        auto batch = [&](float (&cur)[KB][CPL], float (&nxt)[KB][CPL]) {
+            if (kb0 + KB < k1) fetch(nxt, vb, Dv, L, lane, kb0 + KB);
+#pragma unroll
+            for (int k4 = 0; k4 < KB; k4 += 4) {
+                if (kb0 + k4 < k1) {
+                    float4 pr[NR4];
+#pragma unroll
+                    for (int t = 0; t < NR4; ++t)
+                        pr[t] = *reinterpret_cast<const float4 *>(s_S + (4 * t + lr) * spitch + kb0 + k4);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+#pragma unroll
+                        for (int c = 0; c < CPL; ++c)
+#pragma unroll
+                            for (int t = 0; t < NR4; ++t)
+                                acc[c][t] = __builtin_amdgcn_mfma_f32_4x4x1f32(comp(pr[t], q), cur[k4 + q][c],
+                                                                               acc[c][t], 0, 0, 0);
+                }
+            }
+            kb0 += KB;
+        };
+        while (kb0 < k1) {
+            batch(vcur, vnxt);
+            if (kb0 >= k1) break;
+            batch(vnxt, vcur);
+        }
+        const int n = (g * 64 + lane) * CPL;                      // < Dv: every group is whole in this form
+        if (half == 1) {
+#pragma unroll
+            for (int t = 0; t < NR4; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    *reinterpret_cast<float4 *>(s_x + (4 * t + r) * Dv + n) =
+                        make_float4(acc[0][t][r], acc[1][t][r], acc[2][t][r], acc[3][t][r]);
+        }
+        lds_barrier();
+        if (half == 0) {
+#pragma unroll
+            for (int t = 0; t < NR4; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (4 * t + r < ni) {
+                        const float4 o = *reinterpret_cast<const float4 *>(s_x + (4 * t + r) * Dv + n);
+                        const float x[CPL] = {acc[0][t][r] + o.x, acc[1][t][r] + o.y, acc[2][t][r] + o.z,
+                                              acc[3][t][r] + o.w};
+                        ColVec<CPL>::store(&Cb[(size_t)(4 * t + r) * Dv + n], x);
+                    }
+        }
+    }
+};
+
 // The context phase for short key axes (at most 64 keys) and at most one group of 64 columns per wave: a lane owns
 // one column and requests ALL value rows of it at once, before the softmax, so that they arrive while the block waits
 // for its last scores and normalises them; the products then find their operands in registers.  (With batches of
@@ -836,6 +922,11 @@ __global__ __launch_bounds__(64 * W, NG == 1 ? 4 : 2) void k_fwd_fused(
         cp.start(vb, Dv, L, lane, w);
         softmax();
         cp.run(s_S, spitch, Cb, Dv, Lp, ni, lane, w);
+    } else if (Dv % 256 == 0 && 2 * (Dv / 256) == W && Dv <= Hp) {   // two waves per group of 256 columns
+        ContextSplitKeys<T, RT> cp;
+        cp.start(vb, Dv, L, Lp, lane, w);
+        softmax();
+        cp.run(vb, s_S, spitch, s_e, Cb, Dv, L, ni, lane);
     } else if (Dv >= 1024) {                                    // at least four waves with columns to work on
         ContextPhase<T, RT, 4> cp;
         cp.start(vb, Dv, L, lane, w);

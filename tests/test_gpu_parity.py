@@ -87,6 +87,15 @@ EDGE = [
     ("forward_four_wave_blocks", 3, 19, 100, 512, 64, "f32", [100, 61, 3]),
     ("forward_four_wave_blocks_ragged_h", 2, 9, 70, 300, 12, "f32", None),
     ("forward_eight_wave_streaming_past_512", 2, 9, 70, 516, 12, "f32", None),
+    # context phase with two waves per group of 256 value columns, half of the keys each (eight waves at Dv = 1024,
+    # four at Dv = 512): one to five keys (a second half with no keys), odd and even numbers of four-key chunks,
+    # batches that end inside a chunk; and the forms next to it (value rows wider than the staged query rows, Dv = 768)
+    ("context_key_halves_few_keys", 5, 9, 70, 1024, 1024, "f32", [1, 4, 5, 8, 70]),
+    ("context_key_halves_odd_chunks", 3, 11, 76, 1024, 1024, "f32", [76, 41, 13]),
+    ("context_key_halves_bf16", 2, 9, 50, 1024, 1024, "bf16", [50, 23]),
+    ("context_key_halves_four_waves", 3, 13, 90, 512, 512, "f32", [90, 66, 3]),
+    ("context_whole_keys_values_wider_than_h", 2, 9, 70, 768, 1024, "f32", [70, 9]),
+    ("context_whole_keys_768_columns", 2, 9, 70, 1024, 768, "f32", [70, 9]),
     # dV: a block owns all keys up to four key tiles (Tk <= 64), one key tile beyond; value width not a multiple of 64
     ("dv_all_keys_form_four_tiles", 2, 21, 64, 64, 72, "f32", [64, 17]),
     ("dv_per_tile_form_just_past", 2, 21, 65, 64, 72, "f32", [65, 16]),
