@@ -717,7 +717,7 @@ template <typename T, int NG, int ROWNS, int W>
 __global__ __launch_bounds__(64 * W, NG == 1 ? 4 : 2) void k_fwd_fused(
     const T *__restrict__ Qp, const T *__restrict__ Kp, const T *__restrict__ V, const T *__restrict__ v,
     const int *__restrict__ key_len, float *__restrict__ C, float *__restrict__ P,
-    int B, int Tq, int Tk, int H, int Dv, int tiles, int Hp, int spitch, int ranked) {
+    int B, int Tq, int Tk, int H, int Dv, int tiles, int rows_base, int Hp, int spitch, int ranked) {
     constexpr int RT = 8 * NG;
     constexpr int FW_THREADS = 64 * W;
     constexpr int NB = 32 / W;                                 // 16-byte pieces per thread and staging batch
@@ -738,14 +738,21 @@ __global__ __launch_bounds__(64 * W, NG == 1 ? 4 : 2) void k_fwd_fused(
 
     // v does not depend on the placement: the first batch of its loads leaves before the key counts are read
     // (in wave 0, which reads the key counts and must not queue them behind anything, right after that)
-    const int q4 = Hp / 4;                                    // 16-byte columns per row
+    // The row tile as pieces of 64 lanes x 16 bytes: piece m is slice m % ns of row m / ns; wave w takes pieces
+    // w, w + W, ...  The piece numbers are the same in all lanes, and m * ceil(2^16 / ns) >> 16 = m / ns as long as
+    // m ns < 2^16, so that rows and columns cost scalar multiplications (a division per piece, which is what
+    // `e / q4` on the thread's element number compiled to, was most of the instructions of this phase).
+    const int ns = Hp / FW_SS, n_pc = RT * ns;
+    const int ns_inv = __builtin_amdgcn_readfirstlane((65536 + ns - 1) / ns);
+    auto piece_row = [&](int m) { return (m * ns_inv) >> 16; };
+    auto piece_col = [&](int m, int a) { return (m - a * ns) * FW_SS + 4 * lane; };
     float4 vv[NB];
     auto load_v = [&]() {
 #pragma unroll
         for (int u = 0; u < NB; ++u) {
-            const int e = threadIdx.x + u * FW_THREADS;
-            const int h = 4 * (e % q4);
-            vv[u] = (e < RT * q4 && h < H) ? ld4(v, (size_t)h) : make_float4(0.f, 0.f, 0.f, 0.f);
+            const int m = w + u * W;
+            const int h = piece_col(m, piece_row(m));
+            vv[u] = (m < n_pc && h < H) ? ld4(v, (size_t)h) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
     };
     if (w != 0) load_v();
@@ -757,8 +764,11 @@ __global__ __launch_bounds__(64 * W, NG == 1 ? 4 : 2) void k_fwd_fused(
     b = __builtin_amdgcn_readfirstlane(b);
     tile = __builtin_amdgcn_readfirstlane(tile);
     L = __builtin_amdgcn_readfirstlane(L);
-    const int r0 = (int)(((long long)Tq * tile) / tiles);      // rows are split evenly over the tiles
-    const int ni = (int)(((long long)Tq * (tile + 1)) / tiles) - r0;   // 1..RT
+    // rows are split evenly over the tiles: rows_base = Tq / tiles each (from the host: a division here is a long
+    // subroutine on the vector unit in every wave), the first Tq % tiles of them one more
+    const int rows_extra = Tq - rows_base * tiles;
+    const int r0 = tile * rows_base + min(tile, rows_extra);
+    const int ni = rows_base + (tile < rows_extra ? 1 : 0);   // 1..RT
 
     float *Pb = P + ((size_t)b * Tq + r0) * Tk;
     float *Cb = C + ((size_t)b * Tq + r0) * Dv;
@@ -776,9 +786,9 @@ __global__ __launch_bounds__(64 * W, NG == 1 ? 4 : 2) void k_fwd_fused(
     float4 x[NB];
 #pragma unroll
     for (int u = 0; u < NB; ++u) {
-        const int e = threadIdx.x + u * FW_THREADS;
-        const int a = e / q4, h = 4 * (e % q4);
-        x[u] = (e < RT * q4 && h < H && a < ni) ? ld4(qb, (size_t)a * H + h) : make_float4(0.f, 0.f, 0.f, 0.f);
+        const int m = w + u * W;
+        const int a = piece_row(m), h = piece_col(m, a);
+        x[u] = (m < n_pc && h < H && a < ni) ? ld4(qb + (size_t)a * H, (size_t)h) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
     const int k_lo = deal_begin<W>(L, w);
     const int nk = deal_begin<W>(L, w + 1) - k_lo;
@@ -806,22 +816,22 @@ __global__ __launch_bounds__(64 * W, NG == 1 ? 4 : 2) void k_fwd_fused(
     }
 
     float qe_m = 0.f, c_m = 0.f;
-    for (int e0 = threadIdx.x; e0 < RT * q4; e0 += NB * FW_THREADS) {
-        if (e0 != (int)threadIdx.x) {                          // later batches (H > 1024): loaded here
+    for (int m0 = w; m0 < n_pc; m0 += NB * W) {
+        if (m0 != w) {                                         // later batches (H > 1024): loaded here
 #pragma unroll
             for (int u = 0; u < NB; ++u) {
-                const int e = e0 + u * FW_THREADS;
-                const int a = e / q4, h = 4 * (e % q4);
-                const bool in = e < RT * q4 && h < H;
-                x[u] = (in && a < ni) ? ld4(qb, (size_t)a * H + h) : make_float4(0.f, 0.f, 0.f, 0.f);
+                const int m = m0 + u * W;
+                const int a = piece_row(m), h = piece_col(m, a);
+                const bool in = m < n_pc && h < H;
+                x[u] = (in && a < ni) ? ld4(qb + (size_t)a * H, (size_t)h) : make_float4(0.f, 0.f, 0.f, 0.f);
                 vv[u] = in ? ld4(v, (size_t)h) : make_float4(0.f, 0.f, 0.f, 0.f);
             }
         }
 #pragma unroll
         for (int u = 0; u < NB; ++u) {
-            const int e = e0 + u * FW_THREADS;
-            if (e < RT * q4) {
-                const int a = e / q4, h = 4 * (e % q4);
+            const int m = m0 + u * W;
+            if (m < n_pc) {
+                const int a = piece_row(m), h = piece_col(m, a);
                 const bool row_on = a < ni;
                 float y[4], cc[4];
 #pragma unroll
@@ -994,8 +1004,8 @@ static hipError_t launch_fwd_fused_t(const AttnShape &s, const void *Qp, const v
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     const int ranked = s.B <= FW_MAX_RANKED_B ? 1 : 0;
     k_fwd_fused<T, NG, ROWNS, W><<<(unsigned)grid, 64 * W, lds, st>>>(
-        (const T *)Qp, (const T *)Kp, (const T *)V, (const T *)v, key_len, C, P, s.B, s.Tq, s.Tk, s.H, s.Dv, tiles, Hp,
-        spitch, ranked);
+        (const T *)Qp, (const T *)Kp, (const T *)V, (const T *)v, key_len, C, P, s.B, s.Tq, s.Tk, s.H, s.Dv, tiles,
+        s.Tq / tiles, Hp, spitch, ranked);
     return hipGetLastError();
 }
 
