@@ -428,7 +428,7 @@ struct ContextPhase {
         const int n = min((g * 64 + lane) * CPL, Dv - CPL);
 #pragma unroll
         for (int kk = 0; kk < KB; ++kk)
-            ColVec<CPL>::load(vb, (size_t)(unsigned)(min(kb0 + kk, L - 1) * Dv + n), dst[kk]);
+            ColVec<CPL>::load(vb + (size_t)(unsigned)(min(kb0 + kk, L - 1) * Dv), (size_t)n, dst[kk]);   // scalar row, lane column
     }
     __device__ __forceinline__ void start(const T *vb, int Dv, int L, int lane, int w) {
         const int n_grp = (Dv + 64 * CPL - 1) / (64 * CPL);
@@ -514,7 +514,7 @@ struct ContextSplitKeys {
         const int n = min((g * 64 + lane) * CPL, Dv - CPL);
 #pragma unroll
         for (int kk = 0; kk < KB; ++kk)
-            ColVec<CPL>::load(vb, (size_t)(unsigned)(min(kb0 + kk, L - 1) * Dv + n), dst[kk]);
+            ColVec<CPL>::load(vb + (size_t)(unsigned)(min(kb0 + kk, L - 1) * Dv), (size_t)n, dst[kk]);   // scalar row, lane column
     }
     __device__ __forceinline__ void start(const T *vb, int Dv, int L, int Lp, int lane, int w) {
         const int n_grp = (Dv + 64 * CPL - 1) / (64 * CPL);
@@ -601,7 +601,7 @@ struct ContextAllRows {
         for (int g = 0; g < 4; ++g) {
             if (16 * g < Lp) {                                   // uniform
 #pragma unroll
-                for (int kk = 0; kk < 16; ++kk) v[g][kk] = ld(vb, (size_t)(unsigned)(min(16 * g + kk, L - 1) * Dv + n));
+                for (int kk = 0; kk < 16; ++kk) v[g][kk] = ld(vb + (size_t)(unsigned)(min(16 * g + kk, L - 1) * Dv), (size_t)n);
             } else {
 #pragma unroll
                 for (int kk = 0; kk < 16; ++kk) v[g][kk] = 0.f;
