@@ -599,12 +599,9 @@ struct ContextAllRows {
         const int Lp = (L + 3) & ~3;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            if (16 * g < Lp) {                                   // uniform
+            if (16 * g < Lp) {                                   // uniform; run() reads a group under the same condition
 #pragma unroll
                 for (int kk = 0; kk < 16; ++kk) v[g][kk] = ld(vb + (size_t)(unsigned)(min(16 * g + kk, L - 1) * Dv), (size_t)n);
-            } else {
-#pragma unroll
-                for (int kk = 0; kk < 16; ++kk) v[g][kk] = 0.f;
             }
         }
     }
