@@ -38,6 +38,8 @@
 // with light tiles on the others; with more rounds of blocks the heaviest
 // simply start first.  The mapping only moves work around; results do not
 // depend on it.
+#include <type_traits>
+
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -382,6 +384,36 @@ __device__ __forceinline__ bool fw_rows_n(int nk, const RawKey<T> (&raw)[NS][NKM
 // The batches of value rows of all of a wave's column groups form one sequence; the loads of the next batch are
 // issued before the current one is multiplied.  Keys past L carry P = 0, the last valid row stands in for them;
 // no branches around the loads, so that they stay in flight across the arithmetic of the batch before.
+// Rows of a matrix read through a buffer descriptor: element address = base + vector byte offset + scalar byte offset,
+// both 32-bit, range-checked by the hardware against the n_elems elements the descriptor covers (a load past them
+// returns zero).  The descriptor's last word is the raw 32-bit data format of this architecture family.
+template <typename T> struct BufferRows {
+    __amdgpu_buffer_rsrc_t rsrc;
+    __device__ __forceinline__ BufferRows(const T *base, unsigned n_elems)
+        : rsrc(__builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(base), 0, (int)(n_elems * (unsigned)sizeof(T)),
+                                                  0x00020000)) {}
+    // the element as loaded (16-bit types: the bits, zero-extended); value() turns it into the number.  Two steps so
+    // that nothing but the load sits where the loads are issued (an operation on the loaded value there makes the
+    // compiler wait for every load in turn)
+    using Raw = std::conditional_t<sizeof(T) == 4, float, unsigned short>;
+    __device__ __forceinline__ Raw load_raw(unsigned v_off, unsigned s_off) const {
+        if constexpr (sizeof(T) == 4) {
+            return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, v_off, s_off, 0));
+        } else {
+            return __builtin_amdgcn_raw_buffer_load_b16(rsrc, v_off, s_off, 0);
+        }
+    }
+    // (16-bit types: the empty statement keeps the conversion behind whatever barrier precedes the call)
+    static __device__ __forceinline__ float value(Raw raw) {
+        if constexpr (sizeof(T) == 4) {
+            return raw;
+        } else {
+            asm volatile("" : "+v"(raw));
+            return __uint_as_float((unsigned)raw << 16);
+        }
+    }
+};
+
 template <int CPL> struct ColVec;
 template <> struct ColVec<1> {
     static __device__ __forceinline__ void load(const float *p, size_t i, float (&d)[1]) { d[0] = p[i]; }
@@ -593,15 +625,23 @@ struct ContextSplitKeys {
 template <typename T, int RT>
 struct ContextAllRows {
     static constexpr int NR4 = RT / 4;
-    float v[4][16];
+    typename BufferRows<T>::Raw v[4][16];
     __device__ __forceinline__ void start(const T *vb, int Dv, int L, int lane, int w) {
         const int n = min(w * 64 + lane, Dv - 1);
         const int Lp = (L + 3) & ~3;
+        // Buffer loads: the lane's column is the vector offset, the same for all rows, and the row a scalar offset, so
+        // nothing is written to vector registers between the loads.  With 64-bit addresses per lane the compiler
+        // recycled eight address registers and put waits for the loads already under way in front of every
+        // further group of eight: the "all rows at once" took a trip to memory per group.  The descriptor covers the
+        // sample's valid rows (the hardware checks the range); rows L .. Lp - 1 repeat the last one.
+        const BufferRows<T> rows(vb, (unsigned)L * (unsigned)Dv);
+        const unsigned col = (unsigned)n * (unsigned)sizeof(T);
+        const unsigned pitch = (unsigned)Dv * (unsigned)sizeof(T);
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             if (16 * g < Lp) {                                   // uniform; run() reads a group under the same condition
 #pragma unroll
-                for (int kk = 0; kk < 16; ++kk) v[g][kk] = ld(vb + (size_t)(unsigned)(min(16 * g + kk, L - 1) * Dv), (size_t)n);
+                for (int kk = 0; kk < 16; ++kk) v[g][kk] = rows.load_raw(col, (unsigned)min(16 * g + kk, L - 1) * pitch);
             }
         }
     }
@@ -623,10 +663,12 @@ struct ContextAllRows {
                     for (int t = 0; t < NR4; ++t)
                         pr[t] = *reinterpret_cast<const float4 *>(s_S + (4 * t + lr) * spitch + 16 * g + k4);
 #pragma unroll
-                    for (int q = 0; q < 4; ++q)
+                    for (int q = 0; q < 4; ++q) {
+                        const float vq = BufferRows<T>::value(v[g][k4 + q]);
 #pragma unroll
                         for (int t = 0; t < NR4; ++t)
-                            acc[t] = __builtin_amdgcn_mfma_f32_4x4x1f32(comp(pr[t], q), v[g][k4 + q], acc[t], 0, 0, 0);
+                            acc[t] = __builtin_amdgcn_mfma_f32_4x4x1f32(comp(pr[t], q), vq, acc[t], 0, 0, 0);
+                    }
                 }
             }
         }
