@@ -414,6 +414,44 @@ template <typename T> struct BufferRows {
     }
 };
 
+// CPL consecutive columns of one row as they come from memory through a buffer descriptor (f32: CPL words;
+// 16-bit types: CPL / 2 words, one for CPL = 1).  Loading and converting are separate steps: see BufferRows.
+template <typename T, int CPL> struct RowPiece {
+    static constexpr int kBytes = CPL * (int)sizeof(T);
+    static constexpr int NW = (kBytes + 3) / 4;
+    unsigned w[NW];
+    __device__ __forceinline__ void load(const BufferRows<T> &rows, unsigned v_off, unsigned s_off) {
+        if constexpr (kBytes == 2) {
+            w[0] = __builtin_amdgcn_raw_buffer_load_b16(rows.rsrc, v_off, s_off, 0);
+        } else if constexpr (kBytes == 4) {
+            w[0] = __builtin_amdgcn_raw_buffer_load_b32(rows.rsrc, v_off, s_off, 0);
+        } else if constexpr (kBytes == 8) {
+            const auto x = __builtin_amdgcn_raw_buffer_load_b64(rows.rsrc, v_off, s_off, 0);
+            w[0] = x[0];
+            w[1] = x[1];
+        } else {
+            static_assert(kBytes == 16, "one to four columns of 2 or 4 bytes");
+            const auto x = __builtin_amdgcn_raw_buffer_load_b128(rows.rsrc, v_off, s_off, 0);
+            w[0] = x[0];
+            w[1] = x[1];
+            w[2] = x[2];
+            w[3] = x[3];
+        }
+    }
+    // 16-bit types: call before value(), at the place where the conversions may begin
+    __device__ __forceinline__ void pin() {
+        if constexpr (sizeof(T) == 2) {
+#pragma unroll
+            for (int i = 0; i < NW; ++i) asm volatile("" : "+v"(w[i]));
+        }
+    }
+    __device__ __forceinline__ float value(int c) const {
+        if constexpr (sizeof(T) == 4) return __uint_as_float(w[c]);
+        else if constexpr (CPL == 1) return __uint_as_float(w[0] << 16);
+        else return __uint_as_float((c & 1) ? (w[c >> 1] & 0xffff0000u) : (w[c >> 1] << 16));
+    }
+};
+
 template <int CPL> struct ColVec;
 template <> struct ColVec<1> {
     static __device__ __forceinline__ void load(const float *p, size_t i, float (&d)[1]) { d[0] = p[i]; }
@@ -453,14 +491,18 @@ template <typename T, int RT, int CPL>
 struct ContextPhase {
     static constexpr int KB = CPL == 4 ? 8 : FW_KB;     // value rows per batch (two batches in flight per wave)
     static constexpr int NR4 = RT / 4;
-    float vcur[KB][CPL], vnxt[KB][CPL];
+    typedef RowPiece<T, CPL> Piece;
+    Piece vcur[KB], vnxt[KB];
 
-    // rows kb0 .. kb0 + KB - 1 of column group g
-    __device__ __forceinline__ void fetch(float (&dst)[KB][CPL], const T *vb, int Dv, int L, int lane, int g, int kb0) {
-        const int n = min((g * 64 + lane) * CPL, Dv - CPL);
+    // rows kb0 .. kb0 + KB - 1 of column group g.  Buffer loads (lane column as vector offset, row as scalar offset):
+    // with a 64-bit address per lane and load the compiler recycled the address registers and made every batch wait
+    // for the one before it, so that only one batch was ever under way.
+    __device__ __forceinline__ void fetch(Piece (&dst)[KB], const T *vb, int Dv, int L, int lane, int g, int kb0) {
+        const BufferRows<T> rows(vb, (unsigned)L * (unsigned)Dv);
+        const unsigned col = (unsigned)min((g * 64 + lane) * CPL, Dv - CPL) * (unsigned)sizeof(T);
+        const unsigned pitch = (unsigned)Dv * (unsigned)sizeof(T);
 #pragma unroll
-        for (int kk = 0; kk < KB; ++kk)
-            ColVec<CPL>::load(vb + (size_t)(unsigned)(min(kb0 + kk, L - 1) * Dv), (size_t)n, dst[kk]);   // scalar row, lane column
+        for (int kk = 0; kk < KB; ++kk) dst[kk].load(rows, col, (unsigned)min(kb0 + kk, L - 1) * pitch);
     }
     __device__ __forceinline__ void start(const T *vb, int Dv, int L, int lane, int w) {
         const int n_grp = (Dv + 64 * CPL - 1) / (64 * CPL);
@@ -478,13 +520,15 @@ struct ContextPhase {
         int g = w, kb0 = 0;
         // one batch of value rows: products of `cur`, whose successor goes into `nxt` meanwhile; the two register
         // groups change roles from batch to batch (no copies)
-        auto batch = [&](float (&cur)[KB][CPL], float (&nxt)[KB][CPL]) {
+        auto batch = [&](Piece (&cur)[KB], Piece (&nxt)[KB]) {
             int g2 = g, kb2 = kb0 + KB;
             if (kb2 >= Lp) {
                 g2 = g + n_waves;
                 kb2 = 0;
             }
             fetch(nxt, vb, Dv, L, lane, min(g2, n_grp - 1), kb2);
+#pragma unroll
+            for (int kk = 0; kk < KB; ++kk) cur[kk].pin();
 #pragma unroll
             for (int k4 = 0; k4 < KB; k4 += 4) {
                 if (kb0 + k4 < Lp) {
@@ -498,7 +542,7 @@ struct ContextPhase {
                         for (int c = 0; c < CPL; ++c)
 #pragma unroll
                             for (int t = 0; t < NR4; ++t)
-                                acc[c][t] = __builtin_amdgcn_mfma_f32_4x4x1f32(comp(pr[t], q), cur[k4 + q][c],
+                                acc[c][t] = __builtin_amdgcn_mfma_f32_4x4x1f32(comp(pr[t], q), cur[k4 + q].value(c),
                                                                                acc[c][t], 0, 0, 0);
                 }
             }
@@ -539,14 +583,16 @@ struct ContextPhase {
 template <typename T, int RT>
 struct ContextSplitKeys {
     static constexpr int CPL = 4, KB = 8, NR4 = RT / 4;
-    float vcur[KB][CPL], vnxt[KB][CPL];
+    typedef RowPiece<T, CPL> Piece;
+    Piece vcur[KB], vnxt[KB];
     int g, half, k0, k1;                // column group, which half of the keys, keys k0 .. k1 - 1 (multiples of 4)
 
-    __device__ __forceinline__ void fetch(float (&dst)[KB][CPL], const T *vb, int Dv, int L, int lane, int kb0) {
-        const int n = min((g * 64 + lane) * CPL, Dv - CPL);
+    __device__ __forceinline__ void fetch(Piece (&dst)[KB], const T *vb, int Dv, int L, int lane, int kb0) {
+        const BufferRows<T> rows(vb, (unsigned)L * (unsigned)Dv);
+        const unsigned col = (unsigned)min((g * 64 + lane) * CPL, Dv - CPL) * (unsigned)sizeof(T);
+        const unsigned pitch = (unsigned)Dv * (unsigned)sizeof(T);
 #pragma unroll
-        for (int kk = 0; kk < KB; ++kk)
-            ColVec<CPL>::load(vb + (size_t)(unsigned)(min(kb0 + kk, L - 1) * Dv), (size_t)n, dst[kk]);   // scalar row, lane column
+        for (int kk = 0; kk < KB; ++kk) dst[kk].load(rows, col, (unsigned)min(kb0 + kk, L - 1) * pitch);
     }
     __device__ __forceinline__ void start(const T *vb, int Dv, int L, int Lp, int lane, int w) {
         const int n_grp = (Dv + 64 * CPL - 1) / (64 * CPL);
@@ -566,8 +612,10 @@ struct ContextSplitKeys {
 #pragma unroll
             for (int t = 0; t < NR4; ++t) acc[c][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
         int kb0 = k0;
-        auto batch = [&](float (&cur)[KB][CPL], float (&nxt)[KB][CPL]) {
+        auto batch = [&](Piece (&cur)[KB], Piece (&nxt)[KB]) {
             if (kb0 + KB < k1) fetch(nxt, vb, Dv, L, lane, kb0 + KB);
+#pragma unroll
+            for (int kk = 0; kk < KB; ++kk) cur[kk].pin();
 #pragma unroll
             for (int k4 = 0; k4 < KB; k4 += 4) {
                 if (kb0 + k4 < k1) {
@@ -581,7 +629,7 @@ struct ContextSplitKeys {
                         for (int c = 0; c < CPL; ++c)
 #pragma unroll
                             for (int t = 0; t < NR4; ++t)
-                                acc[c][t] = __builtin_amdgcn_mfma_f32_4x4x1f32(comp(pr[t], q), cur[k4 + q][c],
+                                acc[c][t] = __builtin_amdgcn_mfma_f32_4x4x1f32(comp(pr[t], q), cur[k4 + q].value(c),
                                                                                acc[c][t], 0, 0, 0);
                 }
             }
