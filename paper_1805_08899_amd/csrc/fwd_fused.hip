@@ -763,8 +763,11 @@ __device__ __forceinline__ bool fw_pick_item(const int *__restrict__ key_len, in
         const int lane = lane_id();
         const int c0 = lane, c1 = lane + 64;
         // larger key = more valid keys, ties to the lower index; bits: length above 7 bits of (127 - index)
-        const unsigned key0 = c0 < B ? ((unsigned)clamp_len(key_len[c0], Tk) << 7) | (unsigned)(127 - c0) : 0u;
-        const unsigned key1 = c1 < B ? ((unsigned)clamp_len(key_len[c1], Tk) << 7) | (unsigned)(127 - c1) : 0u;
+        // both counts are requested before either is used (as two guarded loads the second left only after the
+        // first had arrived: a second trip to memory for batches of more than 64)
+        const int len0 = key_len[min(c0, B - 1)], len1 = key_len[min(c1, B - 1)];
+        const unsigned key0 = c0 < B ? ((unsigned)clamp_len(len0, Tk) << 7) | (unsigned)(127 - c0) : 0u;
+        const unsigned key1 = c1 < B ? ((unsigned)clamp_len(len1, Tk) << 7) | (unsigned)(127 - c1) : 0u;
         unsigned long long act0 = __ballot(c0 < B), act1 = __ballot(c1 < B);
         int r = (m / 2) * (2 * FW_XCD) + ((m & 1) ? 2 * FW_XCD - 1 - xcd : xcd);   // keys larger than the wanted one
         const int top = 7 + 32 - __builtin_clz((unsigned)Tk);                        // bits in use

@@ -104,6 +104,22 @@ __device__ __forceinline__ void rc_tile_n(int ni, int live, const float (&fq)[RC
 #undef RC_CASE
 }
 
+// An element as loaded, and the number it stands for, as two steps: a load that sits in a guarded branch together
+// with the first operation on its value (for bf16 the shift that widens it) makes the compiler wait for the load
+// inside that branch, one trip to memory per load.  The raw form is what the load instruction delivers (bf16: the
+// 16 bits, zero-extended); zero stands for zero in both.
+template <typename T> struct RawElem;
+template <> struct RawElem<float> {
+    typedef float type;
+    static __device__ __forceinline__ type load(const float *p, size_t i) { return p[i]; }
+    static __device__ __forceinline__ float value(type r) { return r; }
+};
+template <> struct RawElem<bf16_t> {
+    typedef unsigned type;
+    static __device__ __forceinline__ type load(const bf16_t *p, size_t i) { return p[i].bits; }
+    static __device__ __forceinline__ float value(type r) { return __uint_as_float(r << 16); }
+};
+
 template <typename T, bool STASH>
 __global__ __launch_bounds__(RC_THREADS) void k_recompute(
     const T *__restrict__ Qp, const T *__restrict__ Kp, const T *__restrict__ v,
@@ -129,8 +145,9 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
     const int h = blockIdx.x * 64 + lane;
     const bool hv = h < H;
     const int hc = hv ? h : H - 1;
-    const float vh = hv ? ld(v, hc) : 0.f;
-    const float v4 = 4.f * vh;
+    // v of this lane's h: requested here, first touched behind the first loads of a pass (as a guarded load followed
+    // by its scaling the compiler waited for it on the spot: a trip to memory before anything else had been requested)
+    float v_raw = ld(v, hc);
 
     float *dQb = dQp ? dQp + (size_t)b * Tq * H : nullptr;
     float *dKb = dKp + (size_t)b * Tk * H;
@@ -143,13 +160,15 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
         for (int i = w; i < Tq; i += RC_W)
             if (hv) dQb[(size_t)i * H + h] = 0.f;
     }
-    if (w == RC_W - 1) {
-        // sum of this sample's dS (zero in exact arithmetic): the part of sum dS t that comes from t = 1 - 2r
+    // sum of this sample's dS (zero in exact arithmetic): the part of sum dS t that comes from t = 1 - 2r.  The last
+    // wave adds it up behind the first loads of the first pass, so that its rows are not a trip to memory late.
+    auto sum_rows = [&]() {
         float rs = 0.f;
         for (int i = lane; i < Tq; i += 64) rs += ds_rowsum[(size_t)b * Tq + i];
         rs = wave_sum(rs);
         if (lane == 0) s_rowsum = rs;
-    }
+    };
+    if (L == 0 && w == RC_W - 1) sum_rows();
 
     float accV[4] = {0.f, 0.f, 0.f, 0.f};
     if (L > 0) {
@@ -163,16 +182,21 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
         // the pass; the loads are issued before the current tile is evaluated and
         // committed to the other LDS buffer after it.
         const int t_row = threadIdx.x / RC_RJ, t_col = threadIdx.x % RC_RJ;
-        float kx = 0.f, dx = 0.f;
+        typedef RawElem<T> Raw;
+        typename Raw::type kx_raw = 0;
+        float dx = 0.f;
         auto fetch = [&](int jt, int i_pass0, int nrows) {
             const int j = jt * RC_RJ + w;
-            kx = (!STASH && j < L) ? ld(kb, (size_t)j * H + hc) : 0.f;
+            kx_raw = 0;
+            if (!STASH && j < L) kx_raw = Raw::load(kb, (size_t)j * H + hc);
             dx = (t_row < nrows) ? dsb[(size_t)(i_pass0 + t_row) * pitch + jt * RC_RJ + t_col] : 0.f;
         };
         auto commit = [&](int jt, int buf) {
             const int j = jt * RC_RJ + w;
             s_ds[buf][threadIdx.x] = dx;
             if (STASH) return;
+            asm volatile("" : "+v"(kx_raw));
+            const float kx = Raw::value(kx_raw);
             s_sk[buf][w][lane] = kTwoLog2e * kx;
             s_fk[buf][w][lane] = (j < L) ? fast_exp2(kTwoLog2e * kx) : 0.f;
             const int big = __any(fabsf(kx) > kFactorLimit) ? 1 : 0;
@@ -190,9 +214,20 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
             float fq[RC_RI], sq[RC_RI], accQ[RC_RI];
             bool qbig = false;
             {
+                typename Raw::type xr[RC_RI];
+#pragma unroll
+                for (int a = 0; a < RC_RI; ++a) {
+                    xr[a] = 0;
+                    if (!STASH && a < ni) xr[a] = Raw::load(qb, (size_t)(i0 + a) * H + hc);
+                }
+                if (pass == 0 && w == RC_W - 1) sum_rows();
+                asm volatile("" : "+v"(v_raw));
                 float x[RC_RI];
 #pragma unroll
-                for (int a = 0; a < RC_RI; ++a) x[a] = (!STASH && a < ni) ? ld(qb, (size_t)(i0 + a) * H + hc) : 0.f;
+                for (int a = 0; a < RC_RI; ++a) {
+                    asm volatile("" : "+v"(xr[a]));
+                    x[a] = Raw::value(xr[a]);
+                }
 #pragma unroll
                 for (int a = 0; a < RC_RI; ++a) {
                     accQ[a] = 0.f;
@@ -201,6 +236,7 @@ __global__ __launch_bounds__(RC_THREADS) void k_recompute(
                     fq[a] = fast_exp2(sq[a]);
                 }
             }
+            const float v4 = hv ? 4.f * v_raw : 0.f;
             const bool wave_qbig = __any(qbig);
             commit(0, 0);
             lds_barrier();
