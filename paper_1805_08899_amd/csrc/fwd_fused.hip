@@ -836,13 +836,15 @@ __global__ __launch_bounds__(64 * W, NG == 1 ? 4 : 2) void k_fwd_fused(
     const int ns_inv = __builtin_amdgcn_readfirstlane((65536 + ns - 1) / ns);
     auto piece_row = [&](int m) { return (m * ns_inv) >> 16; };
     auto piece_col = [&](int m, int a) { return (m - a * ns) * FW_SS + 4 * lane; };
-    float4 vv[NB];
+    // (v and the query rows stay as loaded until the staging loop: see RawKey)
+    RawKey<T> vv[NB];
     auto load_v = [&]() {
 #pragma unroll
         for (int u = 0; u < NB; ++u) {
             const int m = w + u * W;
             const int h = piece_col(m, piece_row(m));
-            vv[u] = (m < n_pc && h < H) ? ld4(v, (size_t)h) : make_float4(0.f, 0.f, 0.f, 0.f);
+            if (m < n_pc && h < H) vv[u].load(v, (size_t)h);
+            else vv[u].zero();
         }
     };
     if (w != 0) load_v();
@@ -873,12 +875,13 @@ __global__ __launch_bounds__(64 * W, NG == 1 ? 4 : 2) void k_fwd_fused(
     // mode: the first slice); then A: exp(2q)/v and 1/v to LDS (rows past ni and columns past H: 0 and kHugeC)
     const T *qb = Qp + ((size_t)b * Tq + r0) * H;
     const T *kb = Kp + (size_t)b * Tk * H;
-    float4 x[NB];
+    RawKey<T> x[NB];
 #pragma unroll
     for (int u = 0; u < NB; ++u) {
         const int m = w + u * W;
         const int a = piece_row(m), h = piece_col(m, a);
-        x[u] = (m < n_pc && h < H && a < ni) ? ld4(qb + (size_t)a * H, (size_t)h) : make_float4(0.f, 0.f, 0.f, 0.f);
+        if (m < n_pc && h < H && a < ni) x[u].load(qb + (size_t)a * H, (size_t)h);
+        else x[u].zero();
     }
     const int k_lo = deal_begin<W>(L, w);
     const int nk = deal_begin<W>(L, w + 1) - k_lo;
@@ -913,9 +916,16 @@ __global__ __launch_bounds__(64 * W, NG == 1 ? 4 : 2) void k_fwd_fused(
                 const int m = m0 + u * W;
                 const int a = piece_row(m), h = piece_col(m, a);
                 const bool in = m < n_pc && h < H;
-                x[u] = (in && a < ni) ? ld4(qb + (size_t)a * H, (size_t)h) : make_float4(0.f, 0.f, 0.f, 0.f);
-                vv[u] = in ? ld4(v, (size_t)h) : make_float4(0.f, 0.f, 0.f, 0.f);
+                if (in && a < ni) x[u].load(qb + (size_t)a * H, (size_t)h);
+                else x[u].zero();
+                if (in) vv[u].load(v, (size_t)h);
+                else vv[u].zero();
             }
+        }
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            x[u].pin();
+            vv[u].pin();
         }
 #pragma unroll
         for (int u = 0; u < NB; ++u) {
@@ -923,13 +933,14 @@ __global__ __launch_bounds__(64 * W, NG == 1 ? 4 : 2) void k_fwd_fused(
             if (m < n_pc) {
                 const int a = piece_row(m), h = piece_col(m, a);
                 const bool row_on = a < ni;
+                const float4 x4 = x[u].get(), v4 = vv[u].get();
                 float y[4], cc[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const float vq = comp(vv[u], q);
+                    const float vq = comp(v4, q);
                     const bool v_on = fabsf(vq) >= kTinyV;         // false for columns past H (v read as 0)
                     cc[q] = v_on ? fast_rcp(vq) : kHugeC;
-                    y[q] = (v_on && row_on) ? fast_exp2(kTwoLog2e * comp(x[u], q)) * cc[q] : 0.f;
+                    y[q] = (v_on && row_on) ? fast_exp2(kTwoLog2e * comp(x4, q)) * cc[q] : 0.f;
                     qe_m = fmaxf(qe_m, fabsf(y[q]));
                     // a |v| so large that products of two 1/v could underflow also goes to the exact path
                     c_m = fmaxf(c_m, fabsf(vq) > 1e15f ? INFINITY : fabsf(cc[q]));
