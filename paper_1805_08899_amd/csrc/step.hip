@@ -75,10 +75,14 @@ __global__ __launch_bounds__(ST_THREADS) void k_step_bwd(
         oldv0[u] = DEFER ? 0.f : dVb[(size_t)j * Dv + c0];
     }
     const float sq = kTwoLog2e * ld(Qp, (size_t)b * H + hc);
-    const float v4 = hv ? 4.f * ld(v, (size_t)hc) : 0.f;
+    float v_raw = ld(v, (size_t)hc);     // scaled behind the barrier below: as a guarded load with its scaling it was
+                                         // awaited on the spot, before the loads of the dP loop had been requested
 
-    // ---- dP[j] = sum_d dC[d] V[j,d] for this wave's keys of every batch; P to LDS
-    for (int j = threadIdx.x; j < L; j += ST_THREADS) s_p[j] = Pb[j];
+    // ---- dP[j] = sum_d dC[d] V[j,d] for this wave's keys of every batch; P to LDS (its first ST_THREADS entries are
+    //      requested here and stored behind the loop: stored at once, they were a trip to memory that the loads of the
+    //      loop had to wait for)
+    const int jp = min((int)threadIdx.x, L - 1);
+    const float p_first = Pb[jp];
     for (int n = 0; n < n_batch; ++n) {
         const int j0 = 8 * ST_KB * n + ST_KB * w;
         if (j0 >= L) break;                                       // wave-uniform
@@ -98,7 +102,11 @@ __global__ __launch_bounds__(ST_THREADS) void k_step_bwd(
             if (lane == 0 && j0 + u < L) s_dp[j0 + u] = tot;
         }
     }
+    if ((int)threadIdx.x < L) s_p[threadIdx.x] = p_first;
+    for (int j = threadIdx.x + ST_THREADS; j < L; j += ST_THREADS) s_p[j] = Pb[j];
     __syncthreads();
+    asm volatile("" : "+v"(v_raw));
+    const float v4 = hv ? 4.f * v_raw : 0.f;
 
     // ---- the two row sums, formed by every wave for itself (same arithmetic, same result in all waves)
     float r = 0.f;
