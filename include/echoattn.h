@@ -97,8 +97,9 @@ typedef struct {
  * descriptor).  Workspace contents need not survive between calls and may start in any state: the only
  * state that persists from forward to backward is P (Section 5.1).
  * The forward pass needs none (0 is returned, and echo_attn_fwd then accepts workspace == NULL) whenever its
- * one-kernel form runs, which keeps the scores on chip: H a multiple of 4 and a tile of eight query rows
- * within on-chip memory, i.e. every shape of practical size; otherwise B*Tq*Tk floats for the scores.
+ * one-kernel form runs, which keeps the scores on chip: H a multiple of 4, a tile of eight query rows
+ * within on-chip memory and a sample's V below 2 GiB, i.e. every shape of practical size; otherwise B*Tq*Tk
+ * floats for the scores.
  * Exception, decoder steps: for Tq == 1, Tk <= 64, H and Dv multiples of 4 up to 512 and B <= 64 the forward call
  * asks for 4 KB per sample, through which the four blocks that share a sample pass the scores to one another (see
  * echo_attn_fwd). */

@@ -1067,7 +1067,9 @@ static size_t fwd_lds_bytes(const AttnShape &s, int ng) {
 }
 
 bool fwd_fused_supported(const AttnShape &s) {
-    return s.H % 4 == 0 && fwd_lds_bytes(s, 1) <= 150 * 1024;
+    // the context phase addresses a sample's value rows by 32-bit byte offsets (BufferRows)
+    const bool v_in_range = (long long)s.Tk * s.Dv * (s.bf16 ? 2 : 4) < (1LL << 31);
+    return s.H % 4 == 0 && fwd_lds_bytes(s, 1) <= 150 * 1024 && v_in_range;
 }
 
 // Row mode needs the longest key share of a wave, ceil(Tk / 8) keys, times the slices of h to fit the

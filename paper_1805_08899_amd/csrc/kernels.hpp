@@ -39,7 +39,8 @@ inline int ds_pitch(int Tk) { return (Tk + kDsPad - 1) / kDsPad * kDsPad; }
 // F1  scores; tmap != nullptr also writes the tanh map (stash baseline)
 hipError_t launch_score(const AttnShape &s, const void *Qp, const void *Kp, const void *v, const int *key_len,
                         float *S, float *tmap, hipStream_t st);
-// F1+F2+F3 in one kernel (no workspace); needs H to be a multiple of 4 and a row tile that fits LDS
+// F1+F2+F3 in one kernel (no workspace); needs H to be a multiple of 4, a row tile that fits LDS and a sample's
+// value rows below 2 GiB
 bool fwd_fused_supported(const AttnShape &s);
 hipError_t launch_fwd_fused(const AttnShape &s, const void *Qp, const void *Kp, const void *V, const void *v,
                             const int *key_len, float *C, float *P, hipStream_t st);
